@@ -1,0 +1,177 @@
+/*
+ * qmoe — one priority-ordered, preemptible Mixture-of-Experts layer on AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of QLLM (arXiv 2503.09304): the MoE block re-organised into per-expert
+ * FIFO queues (Sec. 3.3, "queues per expert") whose latency-sensitive (LS) entries run before
+ * best-effort (BE) ones (Abstract; Sec. 3.2, Algorithm 1) and which can be stopped at expert
+ * granularity and resumed without repeating finished work (Introduction, "Fine-Grained
+ * Expert-Level Preemption"; Sec. 3.1, "Top-k expert selection").
+ *
+ * One layer-batch goes through
+ *
+ *     moe_route -> moe_permute -> moe_expert_run (any number of calls) -> moe_combine
+ *
+ * Every return of moe_expert_run is a preemption point: the caller may run other contexts (for
+ * instance a newly arrived LS batch) before calling it again with the saved cursor.
+ *
+ * Conventions that hold for every call
+ *  - Pointers marked [device] are GPU global memory owned by the caller; [host] are ordinary host
+ *    pointers.  The library allocates no device memory and creates no stream.  (It allocates one
+ *    small pinned host buffer per context at the first moe_route, freed by moe_destroy.)
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *    work and return, except moe_permute, which waits until the per-expert counts are on the host.
+ *    All calls on one context must be issued on one stream, or be ordered by the caller.
+ *  - Return value: moe_status.  Negative = error; in that case nothing was enqueued and the
+ *    context is unchanged (MOE_E_HIP excepted, where the HIP runtime failed half-way).
+ *    moe_last_error() gives a thread-local description of the last error.
+ *  - Tensors are dense row-major.  dtype MOE_F32: x, weights, y are float.  MOE_BF16: they are
+ *    bfloat16 (16-bit patterns), all products are accumulated in fp32, the SwiGLU activation is
+ *    rounded to bf16 once, y is rounded to bf16 once.  Router logits, gate weights and the
+ *    per-assignment expert outputs are fp32 in both modes.
+ *  - Inputs are assumed finite; behaviour with NaN/Inf is unspecified.
+ *  - For MOE_BF16, H and F must be multiples of 64.
+ */
+#ifndef QMOE_H
+#define QMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque host object: one per in-flight layer-batch */
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef enum {
+    MOE_OK = 0,            /* success; for moe_expert_run: units remain                        */
+    MOE_DONE = 1,          /* moe_expert_run: every unit has been executed                     */
+    MOE_E_ARG = -1,        /* bad argument (null pointer, size out of range, stale cursor)      */
+    MOE_E_STATE = -2,      /* call out of order for this context                                */
+    MOE_E_INCOMPLETE = -3, /* moe_combine asked for a class whose expert work is not finished   */
+    MOE_E_WORKSPACE = -4,  /* workspace too small or misaligned                                 */
+    MOE_E_HIP = -5         /* a HIP runtime call failed                                          */
+} moe_status;
+
+typedef struct {
+    int32_t E;          /* experts, 1..1024                                                     */
+    int32_t k;          /* experts per token, 1..min(E,32)                                      */
+    int32_t H;          /* hidden size                                                          */
+    int32_t F;          /* SwiGLU intermediate size                                             */
+    int32_t dtype;      /* moe_dtype                                                            */
+    int32_t chunk_rows; /* C: most rows of one work unit, 1..256                                */
+    int32_t max_tokens; /* capacity of the context, N <= max_tokens, max_tokens*k < 2^31        */
+} moe_config;
+
+typedef struct {
+    const void *Wg; /* [device] router weight  [H,E]   row-major (E contiguous)                 */
+    const void *W1; /* [device] gate_proj      [E,F,H] (H contiguous)                           */
+    const void *W3; /* [device] up_proj        [E,F,H] (H contiguous)                           */
+    const void *W2; /* [device] down_proj      [E,H,F] (F contiguous)                           */
+} moe_weights;
+
+/* Where a layer-batch stands in its work-unit list.  A plain value: keeping a copy of it (and the
+ * context's workspace) is all a preempted batch needs in order to resume. */
+typedef struct {
+    uint32_t next_unit; /* first unit not yet executed                                          */
+    uint32_t n_units;   /* length of the list                                                   */
+} moe_cursor;
+
+/* One preemptible piece of expert work: `rows` consecutive entries of one expert's queue, all of
+ * one priority class, starting at sorted position `row0`. */
+typedef struct {
+    int32_t expert;
+    int32_t cls; /* 0 = LS, 1 = BE */
+    int32_t row0;
+    int32_t rows; /* 1..chunk_rows */
+} moe_unit;
+
+enum { MOE_CLASS_LS = 1, MOE_CLASS_BE = 2, MOE_CLASS_ALL = 3 };
+
+typedef enum {
+    MOE_GET_LOGITS = 0,     /* float   [N,E]    router logits (bias included)                   */
+    MOE_GET_TOPK_IDX = 1,   /* int32   [N,k]    chosen experts, slot 0 = largest logit          */
+    MOE_GET_TOPK_W = 2,     /* float   [N,k]    renormalised gate weights                       */
+    MOE_GET_COUNTS = 3,     /* int32   [E,2]    queue lengths, column 0 = LS, 1 = BE            */
+    MOE_GET_OFFSETS = 4,    /* int32   [2E+1]   running total in order e0-LS, e0-BE, e1-LS, ... */
+    MOE_GET_PERM = 5,       /* int32   [N*k]    sorted position -> assignment id n*k+slot       */
+    MOE_GET_INV = 6,        /* int32   [N*k]    assignment id -> sorted position                */
+    MOE_GET_EXPERT_OUT = 7, /* float   [N*k,H]  expert output of each sorted position           */
+    MOE_GET_ACT = 8,        /* dtype   [N*k,F]  SwiGLU activation of each sorted position       */
+    MOE_GET_UNITS = 9       /* moe_unit[n_units] the device copy of the work-unit list          */
+} moe_what;
+
+/* Bytes of device workspace a context of this configuration needs; 0 if the configuration is
+ * invalid.  The workspace holds the state a preempted batch must keep (routing metadata, queue
+ * order, finished expert rows: Introduction, paragraph on granular state management; Discussion,
+ * "Limitations") plus scratch. */
+size_t moe_workspace_bytes(const moe_config *cfg);
+
+/* Creates a context over `workspace` ([device], 256-byte aligned, >= moe_workspace_bytes(cfg)).
+ * Touches no GPU state.  The workspace must outlive the context. */
+int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_bytes, moe_ctx **out);
+
+/* Frees the host object (and its pinned buffer).  Does not wait for enqueued work. */
+int32_t moe_destroy(moe_ctx *ctx);
+
+/* Router (Sec. 2.1: "a router that assigns each token to the most relevant experts"; Sec. 2.2).
+ *   logits[n,e] = sum_h x[n,h]*Wg[h,e] + logit_bias[e]      (fp32 accumulation)
+ *   slot j of token n = j-th expert in the order (logit descending, expert index ascending)
+ *   w[n,j] = exp(l_j - l_0) / sum_{i<k} exp(l_i - l_0)      (softmax renormalised over the k)
+ * x [device] [n_tokens,H]; logit_bias [device] float[E] or NULL; 0 <= n_tokens <= max_tokens.
+ * Starts a new layer-batch on the context: earlier results in the workspace are discarded. */
+int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weights *w,
+                  const float *logit_bias, void *stream);
+
+/* Per-expert priority queues (Sec. 3.3 per-expert FIFO; Sec. 3.2 LS before BE): a stable counting
+ * sort of the n_tokens*k assignments by (expert ascending, LS before BE, token ascending).
+ * prio [device] uint8[n_tokens], non-zero = LS.  Produces counts, offsets, perm, inv and the
+ * work-unit list: phase LS then phase BE; inside a phase experts ascending; inside one expert's
+ * sub-queue consecutive chunks of chunk_rows rows, the last one short; empty sub-queues give no
+ * unit.  Waits for the counts (the engine's report to the scheduler after the router stage,
+ * Sec. 3.2) and returns the cursor {0, n_units} in *cursor ([host]). */
+int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void *stream);
+
+/* Expert work, resumable (Sec. 3.1 "Top-k expert selection"; Introduction, contribution 3).
+ * Executes units [cursor->next_unit, min(next_unit + max_units, n_units)) : for each row r of a
+ * unit of expert e, with token n = perm[r] / k,
+ *     act[r,:] = silu(W1[e] x[n,:]) (.) (W3[e] x[n,:]),   out[r,:] = W2[e] act[r,:]
+ * and advances *cursor ([host], in/out).  max_units = UINT32_MAX runs to the end.  x and w must be
+ * the tensors given to moe_route, unchanged.  *cursor must be the value last returned for this
+ * context (MOE_E_ARG otherwise): no unit is ever executed twice.  Results do not depend on how
+ * the unit list is split into calls, bit for bit.
+ * Returns MOE_OK while units remain, MOE_DONE when the list is exhausted. */
+int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t max_units,
+                       moe_cursor *cursor, void *stream);
+
+/* Gate-weighted combine of complete tokens (Sec. 3.1: only fully processed tokens contribute to
+ * the next layer's hidden state):
+ *     y[n,:] = sum_{j=0..k-1, in slot order} w[n,j] * out[inv[n*k+j], :]
+ * accumulated in fp32 from zero in that fixed order, rounded once to the output type.
+ * class_mask selects which tokens' rows of y ([device] [n_tokens,H]) are written: MOE_CLASS_LS,
+ * MOE_CLASS_BE or MOE_CLASS_ALL; rows of other tokens are left untouched.  If a selected class
+ * still has unexecuted units the call fails with MOE_E_INCOMPLETE. */
+int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream);
+
+/* Read-back for tests and schedulers: a [device] pointer into the workspace and its size in bytes
+ * for the current layer-batch.  Valid until the next moe_route on this context. */
+int32_t moe_get(moe_ctx *ctx, int32_t what, const void **dev_ptr, size_t *bytes);
+
+/* Host copy of the context's work-unit list (after moe_permute).  Writes at most `cap` entries to
+ * out ([host], may be NULL when cap is 0) and the full count to *n_units. */
+int32_t moe_units(moe_ctx *ctx, moe_unit *out, uint32_t cap, uint32_t *n_units);
+
+/* The work-unit list as a pure host function of the queue lengths: cnt [host] int32[E][2]
+ * (column 0 = LS).  Same list moe_permute builds.  Needs no GPU. */
+int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_unit *out,
+                       uint32_t cap, uint32_t *n_units);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char *moe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QMOE_H */

@@ -1,0 +1,200 @@
+"""ctypes binding of libqmoe.so: the same calls as include/qmoe.h, argument marshalling only.
+
+Device memory and streams come from PyTorch (torch tensors' data_ptr(), the current stream's
+handle); nothing is computed here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqmoe.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_OK, MOE_DONE = 0, 1
+MOE_E_ARG, MOE_E_STATE, MOE_E_INCOMPLETE, MOE_E_WORKSPACE, MOE_E_HIP = -1, -2, -3, -4, -5
+MOE_CLASS_LS, MOE_CLASS_BE, MOE_CLASS_ALL = 1, 2, 3
+UINT32_MAX = 0xFFFFFFFF
+
+GET = {"logits": 0, "topk_idx": 1, "topk_w": 2, "counts": 3, "offsets": 4, "perm": 5, "inv": 6,
+       "expert_out": 7, "act": 8, "units": 9}
+
+
+class MoeConfig(C.Structure):
+    _fields_ = [("E", C.c_int32), ("k", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
+                ("dtype", C.c_int32), ("chunk_rows", C.c_int32), ("max_tokens", C.c_int32)]
+
+
+class MoeWeights(C.Structure):
+    _fields_ = [("Wg", C.c_void_p), ("W1", C.c_void_p), ("W3", C.c_void_p), ("W2", C.c_void_p)]
+
+
+class MoeCursor(C.Structure):
+    _fields_ = [("next_unit", C.c_uint32), ("n_units", C.c_uint32)]
+
+
+class MoeUnit(C.Structure):
+    _fields_ = [("expert", C.c_int32), ("cls", C.c_int32), ("row0", C.c_int32), ("rows", C.c_int32)]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"qmoe error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2503_09304_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        L.moe_last_error.restype = C.c_char_p
+        L.moe_workspace_bytes.restype = C.c_size_t
+        L.moe_workspace_bytes.argtypes = [C.POINTER(MoeConfig)]
+        L.moe_create.argtypes = [C.POINTER(MoeConfig), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
+        L.moe_destroy.argtypes = [C.c_void_p]
+        L.moe_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(MoeWeights), C.c_void_p, C.c_void_p]
+        L.moe_permute.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeCursor), C.c_void_p]
+        L.moe_expert_run.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.c_uint32,
+                                     C.POINTER(MoeCursor), C.c_void_p]
+        L.moe_combine.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.moe_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
+        L.moe_units.argtypes = [C.c_void_p, C.POINTER(MoeUnit), C.c_uint32, C.POINTER(C.c_uint32)]
+        L.moe_plan_units.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(MoeUnit), C.c_uint32,
+                                     C.POINTER(C.c_uint32)]
+        for f in ("moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
+                  "moe_get", "moe_units", "moe_plan_units"):
+            getattr(L, f).restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def moe_last_error() -> str:
+    return lib().moe_last_error().decode()
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise MoeError(rc, moe_last_error())
+    return rc
+
+
+def moe_workspace_bytes(cfg: MoeConfig) -> int:
+    n = int(lib().moe_workspace_bytes(C.byref(cfg)))
+    if n == 0:
+        raise MoeError(MOE_E_ARG, moe_last_error())
+    return n
+
+
+def moe_plan_units(cnt, E: int, chunk_rows: int):
+    """Host-only: the work-unit list for queue lengths cnt [E][2] (column 0 = LS)."""
+    flat = [int(v) for row in cnt for v in row]
+    arr = (C.c_int32 * len(flat))(*flat)
+    n = C.c_uint32(0)
+    _check(lib().moe_plan_units(arr, E, chunk_rows, None, 0, C.byref(n)))
+    out = (MoeUnit * max(1, n.value))()
+    _check(lib().moe_plan_units(arr, E, chunk_rows, out, n.value, C.byref(n)))
+    return [(u.expert, u.cls, u.row0, u.rows) for u in out[: n.value]]
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+class Context:
+    """One in-flight layer-batch: the opaque moe_ctx plus the torch tensor that backs its workspace.
+    Methods are the C calls with tensors in place of pointers."""
+
+    def __init__(self, E, k, H, F, dtype, chunk_rows, max_tokens, device="cuda:0"):
+        import torch
+        self.cfg = MoeConfig(E, k, H, F, dtype, chunk_rows, max_tokens)
+        self.nbytes = moe_workspace_bytes(self.cfg)
+        self.ws = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
+        assert self.ws.data_ptr() % 256 == 0
+        h = C.c_void_p()
+        _check(lib().moe_create(C.byref(self.cfg), self.ws.data_ptr(), self.nbytes, C.byref(h)))
+        self.h = h
+        self.cursor = MoeCursor(0, 0)
+        self.N = 0
+        self._w = None
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().moe_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def weights(Wg, W1, W3, W2) -> MoeWeights:
+        return MoeWeights(_ptr(Wg), _ptr(W1), _ptr(W3), _ptr(W2))
+
+    def route(self, x, w: MoeWeights, bias=None, n_tokens=None):
+        n = x.shape[0] if n_tokens is None else n_tokens
+        rc = _check(lib().moe_route(self.h, _ptr(x), n, C.byref(w), _ptr(bias), _stream()))
+        self.N, self._w = n, w
+        return rc
+
+    def permute(self, prio) -> MoeCursor:
+        _check(lib().moe_permute(self.h, _ptr(prio), C.byref(self.cursor), _stream()))
+        return self.cursor
+
+    def expert_run(self, x, w: MoeWeights, max_units: int = UINT32_MAX, cursor: Optional[MoeCursor] = None) -> int:
+        cur = self.cursor if cursor is None else cursor
+        return _check(lib().moe_expert_run(self.h, _ptr(x), C.byref(w), max_units, C.byref(cur), _stream()))
+
+    def combine(self, y, class_mask: int = MOE_CLASS_ALL) -> int:
+        return _check(lib().moe_combine(self.h, _ptr(y), class_mask, _stream()))
+
+    def units(self):
+        n = C.c_uint32(0)
+        _check(lib().moe_units(self.h, None, 0, C.byref(n)))
+        out = (MoeUnit * max(1, n.value))()
+        _check(lib().moe_units(self.h, out, n.value, C.byref(n)))
+        return [(u.expert, u.cls, u.row0, u.rows) for u in out[: n.value]]
+
+    def get(self, what: str):
+        """A tensor view (no copy) of one workspace region of the current layer-batch."""
+        import torch
+        p, nb = C.c_void_p(), C.c_size_t()
+        _check(lib().moe_get(self.h, GET[what], C.byref(p), C.byref(nb)))
+        off = (p.value or 0) - self.ws.data_ptr()
+        raw = self.ws[off: off + nb.value]
+        N, k, E, H, F = self.N, self.cfg.k, self.cfg.E, self.cfg.H, self.cfg.F
+        act_dt = torch.bfloat16 if self.cfg.dtype == MOE_BF16 else torch.float32
+        if what == "logits":
+            return raw.view(torch.float32).view(N, E)
+        if what == "topk_idx":
+            return raw.view(torch.int32).view(N, k)
+        if what == "topk_w":
+            return raw.view(torch.float32).view(N, k)
+        if what == "counts":
+            return raw.view(torch.int32).view(E, 2)
+        if what in ("offsets", "perm", "inv"):
+            return raw.view(torch.int32)
+        if what == "expert_out":
+            return raw.view(torch.float32).view(N * k, H)
+        if what == "act":
+            return raw.view(act_dt).view(N * k, F)
+        if what == "units":
+            return raw.view(torch.int32).view(-1, 4)
+        raise KeyError(what)

@@ -1,0 +1,75 @@
+// Internal declarations shared by the host API and the kernel translation units of libqmoe.
+// Not part of the public ABI (that is include/qmoe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qmoe.h"
+
+namespace qmoe {
+
+constexpr int kPermBlock = 1024;  // assignments ranked by one workgroup of the counting sort
+constexpr int kMaxExperts = 256;  // 2*E bucket counters of a 16-wave workgroup must fit in LDS
+constexpr int kMaxTopK = 32;
+constexpr int kMaxChunkRows = 256;
+
+// Units with at most this many rows take the K-split down-projection (more workgroups for the
+// weight-streaming shapes).  A property of the unit alone, so a unit's arithmetic never depends
+// on which other units share its launch.
+constexpr int kSmallUnitRows = 64;
+
+struct RouteArgs {
+    const void *x;
+    const void *Wg;
+    const float *bias;
+    void *WgT;  // scratch: bf16 [E16][H], Wg transposed and padded to a multiple of 16 experts
+    float *logits;
+    int32_t *topk_idx;
+    float *topk_w;
+    int N, H, E, k, dtype;
+};
+hipError_t launch_route(const RouteArgs &a, hipStream_t s);
+
+struct PermuteArgs {
+    const int32_t *topk_idx;
+    const uint8_t *prio;
+    int N, E, k, C;
+    int32_t *cnt;       // [E][2]
+    int32_t *off;       // [2E+1]
+    int32_t *perm;      // [A]
+    int32_t *inv;       // [A]
+    int32_t *rank;      // scratch [A]
+    int32_t *blockoff;  // scratch [nblocks][2E]
+    uint8_t *cls;       // [N] 0 = LS, 1 = BE
+    moe_unit *units;    // device unit list
+    int32_t *n_units;   // device scalar
+    int32_t max_units;
+};
+hipError_t launch_permute(const PermuteArgs &a, hipStream_t s);
+
+struct ExpertArgs {
+    const void *x;
+    const void *W1, *W3, *W2;
+    const int32_t *perm;
+    const moe_unit *units;  // device list
+    void *act;              // [A,F] dtype
+    float *out;             // [A,H]
+    int H, F, k, dtype;
+    uint32_t u0, nu;        // units [u0, u0+nu)
+    int max_rows;           // largest rows among those units (host copy of the list)
+    bool has_small, has_large;  // unit classes present (rows <= / > kSmallUnitRows)
+};
+hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
+
+struct CombineArgs {
+    const float *out;      // [A,H]
+    const float *topk_w;   // [N,k]
+    const int32_t *inv;    // [A]
+    const uint8_t *cls;    // [N]
+    void *y;               // [N,H] dtype
+    int N, H, k, dtype, class_mask;
+};
+hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
+
+}  // namespace qmoe

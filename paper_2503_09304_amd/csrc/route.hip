@@ -1,0 +1,182 @@
+// Router kernels: gate GEMM (fp32 logits), then per-token top-k with renormalised softmax
+// weights.  Follows the paper's description of the MoE router (Sec. 2.1, Sec. 2.2): each token is
+// assigned to its k most relevant experts.
+//
+// bf16: logits come from 16x16x32 bf16 MFMA tiles (16 tokens x 16 experts per tile), fp32
+// accumulation.  Wg is [H,E] with E contiguous, the wrong majorness for MFMA operands, so a
+// small kernel first writes it transposed (and padded to a multiple of 16 experts) into scratch.
+// A workgroup owns 16 tokens; its 4 waves split the hidden dimension into 4 contiguous ranges and
+// add their partial tiles through LDS in wave order, so the summation order is fixed.
+// fp32: one wave per token, lanes stride the hidden dimension, butterfly reduction.
+// top-k: one wave per token; k rounds of a wave-wide arg-max over (logit desc, index asc).
+#include <hip/hip_runtime.h>
+
+#include "qmoe_internal.h"
+
+namespace qmoe {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void wg_transpose_bf16(const uint16_t *__restrict__ Wg, uint16_t *__restrict__ WgT,
+                                                         int H, int E, int E16) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)E16 * H) return;
+    const int e = (int)(i / H), h = (int)(i % H);
+    WgT[i] = e < E ? Wg[(long)h * E + e] : (uint16_t)0;
+}
+
+// NB = number of 16-expert blocks held in registers (E16 <= 16*NB).
+template <int NB>
+__global__ __launch_bounds__(256) void gate_logits_bf16(const uint16_t *__restrict__ x, const uint16_t *__restrict__ WgT,
+                                                        const float *__restrict__ bias, float *__restrict__ logits,
+                                                        int N, int H, int E, int nb) {
+    __shared__ float red[3][NB][4][64];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int t16 = l & 15, q = l >> 4;
+    int tok = blockIdx.x * 16 + t16;
+    if (tok > N - 1) tok = N - 1;
+    const int steps = H / 32;
+    const int per = (steps + 3) / 4;
+    const int s0 = w * per, s1 = min(steps, s0 + per);
+    f32x4 acc[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t *xa = x + (long)tok * H + q * 8;
+    const uint16_t *wb = WgT + (long)t16 * H + q * 8;
+    for (int s = s0; s < s1; ++s) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(xa + s * 32);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nb) {
+                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(wb + (long)b * 16 * H + s * 32);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[b], 0, 0, 0);
+            }
+        }
+    }
+    if (w > 0) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[w - 1][b][r][l] = acc[b][r];
+    }
+    __syncthreads();
+    if (w == 0) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (b < nb) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = acc[b][r];
+                    v += red[0][b][r][l];
+                    v += red[1][b][r][l];
+                    v += red[2][b][r][l];
+                    const int e = b * 16 + t16;          // D: column = expert
+                    const int t = blockIdx.x * 16 + q * 4 + r;  // D: row = token
+                    if (e < E && t < N) logits[(long)t * E + e] = v + (bias ? bias[e] : 0.f);
+                }
+            }
+        }
+    }
+}
+
+// One wave per token, 8 experts at a time.
+__global__ __launch_bounds__(256) void gate_logits_f32(const float *__restrict__ x, const float *__restrict__ Wg,
+                                                       const float *__restrict__ bias, float *__restrict__ logits,
+                                                       int N, int H, int E) {
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int tok = blockIdx.x * 4 + w;
+    if (tok >= N) return;
+    for (int e0 = 0; e0 < E; e0 += 8) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int h = l; h < H; h += 64) {
+            const float xv = x[(long)tok * H + h];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (e0 + j < E) acc[j] = fmaf(xv, Wg[(long)h * E + e0 + j], acc[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float v = acc[j];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            if (l == 0 && e0 + j < E) logits[(long)tok * E + e0 + j] = v + (bias ? bias[e0 + j] : 0.f);
+        }
+    }
+}
+
+// One wave per token.  Lane l holds the logits of experts l, l+64, l+128, l+192.
+__global__ __launch_bounds__(256) void topk_softmax(const float *__restrict__ logits, int32_t *__restrict__ topk_idx,
+                                                    float *__restrict__ topk_w, int N, int E, int k) {
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int tok = blockIdx.x * 4 + w;
+    if (tok >= N) return;
+    constexpr int SL = kMaxExperts / 64;
+    float v[SL];
+#pragma unroll
+    for (int c = 0; c < SL; ++c) {
+        const int e = l + 64 * c;
+        v[c] = e < E ? logits[(long)tok * E + e] : -INFINITY;
+    }
+    unsigned picked = 0;
+    float my_v = 0.f;
+    int my_e = 0;
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < SL; ++c) {
+            const int e = l + 64 * c;
+            const bool ok = e < E && !((picked >> c) & 1u);
+            if (ok && (be == 0x7fffffff || v[c] > bv)) { bv = v[c]; be = e; }   // ascending e: '>' keeps the lowest index
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oe = __shfl_xor(be, o, 64);
+            const bool take = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
+            if (take) { bv = ov; be = oe; }
+        }
+        if ((be & 63) == l) picked |= 1u << (be >> 6);
+        if (l == j) { my_v = bv; my_e = be; }
+    }
+    const float top = __shfl(my_v, 0, 64);
+    float p = l < k ? expf(my_v - top) : 0.f;
+    float s = p;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (l < k) {
+        topk_idx[(long)tok * k + l] = my_e;
+        topk_w[(long)tok * k + l] = p / s;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_route(const RouteArgs &a, hipStream_t s) {
+    if (a.N <= 0) return hipSuccess;
+    if (a.dtype == MOE_BF16) {
+        const int E16 = (a.E + 15) / 16 * 16, nb = E16 / 16;
+        const long tot = (long)E16 * a.H;
+        hipLaunchKernelGGL(wg_transpose_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s,
+                           (const uint16_t *)a.Wg, (uint16_t *)a.WgT, a.H, a.E, E16);
+        const dim3 g((a.N + 15) / 16), b(256);
+        const uint16_t *x = (const uint16_t *)a.x, *wt = (const uint16_t *)a.WgT;
+        if (nb <= 1) hipLaunchKernelGGL(gate_logits_bf16<1>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+        else if (nb <= 2) hipLaunchKernelGGL(gate_logits_bf16<2>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+        else if (nb <= 4) hipLaunchKernelGGL(gate_logits_bf16<4>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+        else if (nb <= 8) hipLaunchKernelGGL(gate_logits_bf16<8>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+        else hipLaunchKernelGGL(gate_logits_bf16<16>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+    } else {
+        hipLaunchKernelGGL(gate_logits_f32, dim3((a.N + 3) / 4), dim3(256), 0, s, (const float *)a.x,
+                           (const float *)a.Wg, a.bias, a.logits, a.N, a.H, a.E);
+    }
+    hipLaunchKernelGGL(topk_softmax, dim3((a.N + 3) / 4), dim3(256), 0, s, (const float *)a.logits, a.topk_idx,
+                       a.topk_w, a.N, a.E, a.k);
+    return hipGetLastError();
+}
+
+}  // namespace qmoe

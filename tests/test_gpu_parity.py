@@ -1,0 +1,225 @@
+"""GPU path vs CPU oracle, element by element, through the C ABI.  Needs an MI355X (-m gpu).
+
+Integer results (expert indices, counts, offsets, permutation, unit list) are compared
+bit-exactly; floating point within max|err|/RMS(ref) <= 1e-4 (fp32 configs) / 2e-2 (bf16 configs).
+The top-k decision is taken on fp32 logits by the kernel; the oracle's selection code is replayed
+on those logits (must agree everywhere) and the pure-fp64 decision must agree for every token whose
+logit gaps exceed TAU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_09304_amd as q
+import workloads as wl
+from gpu_util import GpuLayer, DevWeights, rel_err, to_host
+
+pytestmark = pytest.mark.gpu
+
+TAU = 1e-4
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def check_layer(inp, cuts=(), sample_tokens=None, dev_w=None):
+    """Full comparison of one layer-batch.  sample_tokens: compare y/O only for these tokens
+    (full-size configs); None = everything."""
+    cfg = inp.cfg
+    say("case", wl.describe(cfg), "cuts", list(cuts))
+    g = GpuLayer(inp, dev_w).full(cuts)
+    r = g.fetch("logits", "topk_idx", "topk_w", "counts", "offsets", "perm", "inv", "units", "y")
+    # ---- oracle on the same bits
+    L64 = oracle.gate_logits(inp.x, inp.w["Wg"], inp.bias)
+    e_logit = rel_err(r["logits"], L64)
+    assert e_logit <= 2e-5, e_logit
+    # (i) replay: the oracle's selection applied to the kernel's fp32 logits
+    idx_rep, wt_rep = oracle.topk(r["logits"].astype(np.float64), cfg.k)
+    assert np.array_equal(idx_rep, r["topk_idx"])
+    np.testing.assert_allclose(r["topk_w"], wt_rep, rtol=0, atol=2e-6)
+    np.testing.assert_allclose(r["topk_w"].astype(np.float64).sum(1), 1.0, atol=1e-6)
+    cnt, off, perm, inv = oracle.queues(r["topk_idx"], inp.prio, cfg.E)
+    assert np.array_equal(cnt, r["counts"]) and np.array_equal(off, r["offsets"])
+    assert np.array_equal(perm, r["perm"]) and np.array_equal(inv, r["inv"])
+    units = oracle.units(cnt, cfg.chunk_rows)
+    assert [tuple(int(v) for v in u) for u in units] == g.ctx.units()
+    assert np.array_equal(units.reshape(-1, 4), r["units"].reshape(-1, 4))
+    assert cnt.sum() == cfg.A
+    # (ii) direct: pure fp64 decision, wherever it is not within TAU of a tie
+    idx64, wt64 = oracle.topk(L64, cfg.k)
+    margin = oracle.topk_margin(L64, cfg.k)
+    clear = margin >= TAU
+    mism = np.any(idx64 != r["topk_idx"], axis=1)
+    say(f"  tokens within {TAU} of a tie: {int((~clear).sum())}; index mismatches vs fp64: {int(mism.sum())}")
+    assert not np.any(mism & clear)
+    assert not mism.any(), "seed chosen so that the fp64 decision matches everywhere"
+    np.testing.assert_allclose(r["topk_w"], wt64, rtol=0, atol=1e-5)
+    # ---- values
+    lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    if sample_tokens is None:
+        lay.run()
+        y_ref, comp = lay.y()
+        assert comp.all()
+        O = to_host(g.ctx.get("expert_out"))
+        e_o = rel_err(O, lay.O)
+        y_got = wl.as_f64(r["y"])
+    else:
+        toks = np.asarray(sample_tokens)
+        y_ref = lay.y_tokens_direct(toks)
+        y_got = wl.as_f64(r["y"])[toks]
+        e_o = float("nan")
+    e_y = rel_err(y_got, y_ref)
+    say(f"  rel err: logits {e_logit:.2e}  expert_out {e_o:.2e}  y {e_y:.2e}  (tol {TOL[cfg.dtype]})")
+    assert np.isfinite(y_got).all()
+    assert e_y <= TOL[cfg.dtype]
+    if sample_tokens is None:
+        assert e_o <= TOL[cfg.dtype]
+    return g, r
+
+
+def bits(t: torch.Tensor) -> torch.Tensor:
+    return t.contiguous().view(torch.uint8)
+
+
+def assert_bit_identical(inp, cuts, dev_w=None, base=None):
+    a = base if base is not None else GpuLayer(inp, dev_w).full(())
+    b = GpuLayer(inp, dev_w or a.dw).full(cuts)
+    assert torch.equal(bits(a.y), bits(b.y)), f"y differs after cuts {cuts}"
+    assert torch.equal(bits(a.ctx.get("expert_out")), bits(b.ctx.get("expert_out"))), f"expert_out differs {cuts}"
+    assert torch.equal(bits(a.ctx.get("act")), bits(b.ctx.get("act")))
+    return a
+
+
+# ------------------------------------------------------------------------------------------------
+def test_cfg1_tiny_fp32_with_preemption_after_expert_1():
+    cfg = wl.CONFIGS["cfg1"]
+    inp = wl.make_inputs(cfg)
+    g, r = check_layer(inp)
+    units = g.ctx.units()
+    # preempt after the last LS-phase unit of expert 1, and (second variant) after its last BE unit
+    for cls in (0, 1):
+        last = max(i for i, u in enumerate(units) if u[0] == 1 and u[1] == cls)
+        assert_bit_identical(inp, (last + 1,), base=g)
+    # every possible single cut, and one multi-cut
+    for c in range(0, len(units) + 1):
+        assert_bit_identical(inp, (c,), base=g)
+    assert_bit_identical(inp, wl.cut_points(11, range(1, len(units)), 4), base=g)
+
+
+def small_cases():
+    base = dict(dtype="bf16", seed=910, E=8, k=2, H=256, F=512, N=300, n_ls=75, chunk_rows=64)
+    yield "bf16_small_units", wl.LayerConfig("s1", **base)
+    yield "bf16_large_units", wl.LayerConfig("s2", **{**base, "N": 1300, "n_ls": 200, "chunk_rows": 256, "seed": 911})
+    yield "bf16_chunk_100", wl.LayerConfig("s3", **{**base, "N": 777, "n_ls": 333, "chunk_rows": 100, "seed": 912})
+    yield "bf16_skew_no_ksplit", wl.LayerConfig("s4", dtype="bf16", seed=913, E=64, k=8, H=128, F=192, N=600,
+                                                n_ls=100, chunk_rows=256, bias_kind="zipf", bias_arg=1.1)
+    yield "bf16_hot_expert0", wl.LayerConfig("s5", **{**base, "N": 64, "n_ls": 16, "bias_kind": "expert0",
+                                                      "bias_arg": 1.5, "seed": 914})
+    yield "f32_ragged", wl.LayerConfig("s6", dtype="f32", seed=915, E=5, k=3, H=100, F=72, N=150, n_ls=40,
+                                       chunk_rows=37)
+    yield "bf16_k1", wl.LayerConfig("s7", **{**base, "k": 1, "seed": 916})
+    yield "bf16_k_equals_E", wl.LayerConfig("s8", **{**base, "E": 4, "k": 4, "N": 90, "n_ls": 30, "seed": 917})
+    yield "bf16_all_ls", wl.LayerConfig("s9", **{**base, "n_ls": 300, "seed": 918})
+    yield "bf16_all_be", wl.LayerConfig("s10", **{**base, "n_ls": 0, "seed": 919})
+    yield "bf16_one_token", wl.LayerConfig("s11", **{**base, "N": 1, "n_ls": 1, "seed": 920})
+    yield "bf16_many_experts", wl.LayerConfig("s12", dtype="bf16", seed=921, E=256, k=6, H=128, F=128, N=257,
+                                              n_ls=64, chunk_rows=32)
+
+
+@pytest.mark.parametrize("name,cfg", list(small_cases()), ids=[n for n, _ in small_cases()])
+def test_reduced_size_cases_match_oracle_and_survive_preemption(name, cfg):
+    inp = wl.make_inputs(cfg)
+    g, r = check_layer(inp)
+    nu = len(g.ctx.units())
+    if nu > 1:
+        assert_bit_identical(inp, wl.cut_points(cfg.seed, range(1, nu), 4), base=g)
+        assert_bit_identical(inp, tuple(range(1, nu)), base=g)          # one unit per call
+
+
+def test_empty_batch_and_k1_weights():
+    cfg = wl.LayerConfig("empty", dtype="bf16", seed=1, E=8, k=2, H=128, F=128, N=0, n_ls=0, chunk_rows=64)
+    inp = wl.make_inputs(cfg)
+    g = GpuLayer(inp, max_tokens=16)
+    cur = g.route_permute()
+    assert cur.n_units == 0
+    assert g.run() == q.MOE_DONE
+    assert g.combine() == q.MOE_OK
+    assert int(g.ctx.get("counts").sum().item()) == 0
+    cfg = wl.LayerConfig("k1", dtype="f32", seed=2, E=6, k=1, H=64, F=64, N=40, n_ls=10, chunk_rows=8)
+    g = GpuLayer(wl.make_inputs(cfg)).full()
+    assert bool((g.ctx.get("topk_w") == 1.0).all())
+
+
+def test_exact_logit_ties_take_the_lowest_expert_index():
+    cfg = wl.LayerConfig("ties", dtype="bf16", seed=3, E=8, k=2, H=128, F=128, N=96, n_ls=24, chunk_rows=32)
+    inp = wl.make_inputs(cfg)
+    wg = inp.w["Wg"]
+    wg[:, 5] = wg[:, 2]          # duplicate columns: bitwise-equal logits for experts 2 and 5
+    wg[:, 7] = wg[:, 2]
+    g = GpuLayer(inp).full()
+    r = g.fetch("logits", "topk_idx", "topk_w")
+    assert np.array_equal(r["logits"][:, 2], r["logits"][:, 5])
+    idx_rep, _ = oracle.topk(r["logits"].astype(np.float64), cfg.k)
+    assert np.array_equal(idx_rep, r["topk_idx"])
+    both = np.isin(r["topk_idx"], [2, 5, 7]).sum(1)
+    assert (both == 2).any()
+    for row in r["topk_idx"][both == 2]:
+        assert list(row) == [2, 5]
+    for row in r["topk_idx"][both == 1]:
+        assert 2 in row and 5 not in row and 7 not in row
+
+
+def test_only_complete_tokens_are_combined_and_call_order_is_enforced():
+    cfg = wl.CONFIGS["cfg1"]
+    inp = wl.make_inputs(cfg)
+    ref = GpuLayer(inp).full()
+    g = GpuLayer(inp)
+    cur = g.route_permute()
+    units = g.ctx.units()
+    n_ls = sum(1 for u in units if u[1] == 0)
+    assert all(u[1] == 0 for u in units[:n_ls]) and all(u[1] == 1 for u in units[n_ls:])
+    g.run(n_ls - 1)
+    with pytest.raises(q.MoeError) as ei:
+        g.combine(q.MOE_CLASS_LS)
+    assert ei.value.code == q.MOE_E_INCOMPLETE
+    g.run(1)
+    assert g.combine(q.MOE_CLASS_LS) == q.MOE_OK
+    with pytest.raises(q.MoeError) as ei:
+        g.combine(q.MOE_CLASS_BE)
+    assert ei.value.code == q.MOE_E_INCOMPLETE
+    torch.cuda.synchronize()
+    ls = torch.from_numpy(inp.prio != 0).to(g.y.device)
+    assert torch.equal(bits(g.y[ls]), bits(ref.y[ls]))          # LS rows final before any BE work ran
+    assert bool(torch.isnan(g.y[~ls]).all())                      # BE rows untouched
+    # a stale cursor is refused: no unit runs twice
+    stale = q.MoeCursor(0, cur.n_units)
+    with pytest.raises(q.MoeError) as ei:
+        g.ctx.expert_run(g.x, g.dw.struct, 1, cursor=stale)
+    assert ei.value.code == q.MOE_E_ARG
+    assert g.run() == q.MOE_DONE
+    g.combine(q.MOE_CLASS_BE)
+    torch.cuda.synchronize()
+    assert torch.equal(bits(g.y), bits(ref.y))
+    with pytest.raises(q.MoeError) as ei:
+        g.ctx.permute(g.prio)
+    assert ei.value.code == q.MOE_E_STATE
+
+
+def test_context_reuse_with_a_smaller_batch_and_run_to_run_identity():
+    big = wl.LayerConfig("r1", dtype="bf16", seed=31, E=8, k=2, H=256, F=512, N=400, n_ls=100, chunk_rows=64)
+    small = wl.scaled(big, N=130, n_ls=30, seed=32)
+    ib, isml = wl.make_inputs(big), wl.make_inputs(small, weights=None)
+    g = GpuLayer(ib).full()
+    y1 = g.y.clone()
+    g.full()
+    assert torch.equal(bits(y1), bits(g.y))
+    # same context, smaller batch
+    g2 = GpuLayer(isml)
+    g2.ctx.close()
+    g2.ctx = g.ctx
+    g2.dw = DevWeights(isml.w)
+    g2.full()
+    ref = GpuLayer(isml).full()
+    assert torch.equal(bits(g2.y), bits(ref.y))

@@ -1,0 +1,95 @@
+"""Parity at the full workload sizes, in the launch configuration the benchmark times.  The
+oracle computes sampled tokens one by one; integer artefacts are compared in full.  Needs an
+MI355X (-m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_09304_amd as q
+import workloads as wl
+from gpu_util import DevWeights, GpuLayer, rel_err, to_host
+from test_gpu_parity import assert_bit_identical, bits, check_layer, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mixtral():
+    w = wl.make_weights(wl.CONFIGS["cfg2"])
+    return w, DevWeights(w)
+
+
+def sample(cfg, n, seed=0):
+    rng = np.random.default_rng([cfg.seed, 555, seed])
+    return np.sort(rng.choice(cfg.N, size=min(n, cfg.N), replace=False))
+
+
+def expert_boundaries(units):
+    """Cursor positions where the expert or the phase changes between consecutive units."""
+    return [i for i in range(1, len(units)) if units[i][0] != units[i - 1][0] or units[i][1] != units[i - 1][1]]
+
+
+def test_cfg2_mixtral_prefill(mixtral):
+    w, dw = mixtral
+    cfg = wl.CONFIGS["cfg2"]
+    inp = wl.make_inputs(cfg, weights=w)
+    g, r = check_layer(inp, sample_tokens=sample(cfg, 24), dev_w=dw)
+    say("  counts [E][LS,BE]:", r["counts"].tolist())
+    units = g.ctx.units()
+    assert_bit_identical(inp, wl.cut_points(cfg.seed, expert_boundaries(units), 4), dev_w=dw, base=g)
+
+
+def test_cfg4_mixtral_decode_hot_expert(mixtral):
+    w, dw = mixtral
+    cfg = wl.CONFIGS["cfg4"]
+    inp = wl.make_inputs(cfg, weights=w)
+    g, r = check_layer(inp, sample_tokens=np.arange(cfg.N), dev_w=dw)
+    share0 = r["counts"][0].sum() / cfg.A
+    say(f"  expert 0 holds {share0:.1%} of the assignments; counts {r['counts'].tolist()}")
+    assert share0 > 0.2
+    units = g.ctx.units()
+    assert_bit_identical(inp, tuple(range(1, len(units))), dev_w=dw, base=g)
+
+
+def test_cfg3_ls_batch_preempts_a_be_prompt(mixtral):
+    w, dw = mixtral
+    cbe, cls_ = wl.CONFIGS["cfg3_be"], wl.CONFIGS["cfg3_ls"]
+    ibe, ils = wl.make_inputs(cbe, weights=w), wl.make_inputs(cls_, weights=w)
+    base, _ = check_layer(ibe, sample_tokens=sample(cbe, 16), dev_w=dw)
+    units = base.ctx.units()
+    assert all(u[1] == 1 for u in units) and max(u[3] for u in units) == 256
+    # BE in flight, one unit per call; after a third of the units the LS batch arrives, runs to
+    # completion on its own context, then BE resumes from its cursor.
+    be = GpuLayer(ibe, dw)
+    cur = be.route_permute()
+    stop = cur.n_units // 3
+    for _ in range(stop):
+        be.run(1)
+    ls = GpuLayer(ils, dw).full()
+    assert be.ctx.cursor.next_unit == stop
+    while be.run(2) != q.MOE_DONE:
+        pass
+    be.combine()
+    torch.cuda.synchronize()
+    assert torch.equal(bits(be.y), bits(base.y))
+    assert torch.equal(bits(be.ctx.get("expert_out")), bits(base.ctx.get("expert_out")))
+    # the LS batch itself is right
+    toks = sample(cls_, 16)
+    lay = oracle.OracleLayer(ils.x, ils.w, ils.prio, ils.bias, cls_.k, cls_.chunk_rows)
+    assert np.array_equal(lay.idx, to_host(ls.ctx.get("topk_idx")))
+    e = rel_err(wl.as_f64(to_host(ls.y))[toks], lay.y_tokens_direct(toks))
+    say(f"  LS batch rel err {e:.2e}")
+    assert e <= 2e-2
+
+
+def test_cfg5_fine_grained_skewed_with_four_preemptions():
+    cfg = wl.CONFIGS["cfg5"]
+    inp = wl.make_inputs(cfg)
+    g, r = check_layer(inp, sample_tokens=sample(cfg, 32))
+    tot = r["counts"].sum(1)
+    say(f"  rows per expert: max {tot.max()} min {tot.min()}; units {len(g.ctx.units())}")
+    units = g.ctx.units()
+    cuts = wl.cut_points(cfg.seed, expert_boundaries(units), 4)
+    assert len(cuts) == 4
+    assert_bit_identical(inp, cuts, base=g)
