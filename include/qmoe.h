@@ -56,7 +56,7 @@ typedef enum {
 } moe_status;
 
 typedef struct {
-    int32_t E;          /* experts, 1..1024                                                     */
+    int32_t E;          /* experts, 1..256                                                      */
     int32_t k;          /* experts per token, 1..min(E,32)                                      */
     int32_t H;          /* hidden size                                                          */
     int32_t F;          /* SwiGLU intermediate size                                             */
@@ -167,6 +167,15 @@ int32_t moe_units(moe_ctx *ctx, moe_unit *out, uint32_t cap, uint32_t *n_units);
  * (column 0 = LS).  Same list moe_permute builds.  Needs no GPU. */
 int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_unit *out,
                        uint32_t cap, uint32_t *n_units);
+
+/* Per-kernel timing for benchmarks.  moe_profile(ctx, 1) makes moe_expert_run bracket each of its
+ * kernel launches with a pair of HIP events on the caller's stream (events are created on demand
+ * and kept by the context); moe_profile(ctx, 0) turns that off.  moe_profile_read waits for the
+ * recorded events, adds up elapsed milliseconds and launch counts per kernel kind since the last
+ * read into ms / launches ([host], MOE_PROF_KINDS entries each) and forgets them. */
+enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN_SMALL = 1, MOE_PROF_DOWN_LARGE = 2, MOE_PROF_KINDS = 3 };
+int32_t moe_profile(moe_ctx *ctx, int32_t enable);
+int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *moe_last_error(void);

@@ -72,7 +72,9 @@ def lib():
         L.moe_units.argtypes = [C.c_void_p, C.POINTER(MoeUnit), C.c_uint32, C.POINTER(C.c_uint32)]
         L.moe_plan_units.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(MoeUnit), C.c_uint32,
                                      C.POINTER(C.c_uint32)]
-        for f in ("moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
+        L.moe_profile.argtypes = [C.c_void_p, C.c_int32]
+        L.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
+        for f in ("moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
                   "moe_get", "moe_units", "moe_plan_units"):
             getattr(L, f).restype = C.c_int32
         _lib = L
@@ -164,6 +166,16 @@ class Context:
 
     def combine(self, y, class_mask: int = MOE_CLASS_ALL) -> int:
         return _check(lib().moe_combine(self.h, _ptr(y), class_mask, _stream()))
+
+    def profile(self, enable: bool) -> None:
+        _check(lib().moe_profile(self.h, 1 if enable else 0))
+
+    def profile_read(self):
+        """{kind: (total ms, launches)} of the expert kernels since the last read."""
+        ms = (C.c_float * 3)()
+        n = (C.c_uint32 * 3)()
+        _check(lib().moe_profile_read(self.h, ms, n))
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(("gate_up", "down_small", "down_large"))}
 
     def units(self):
         n = C.c_uint32(0)

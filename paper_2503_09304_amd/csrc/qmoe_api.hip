@@ -93,6 +93,8 @@ struct moe_ctx {
     int32_t *pinned;  // 2E counts + 1 unit count, pinned host memory (allocated at first route)
     const void *x;
     moe_weights w;
+    qmoe::Profiler prof;
+    bool prof_on;
 };
 
 namespace {
@@ -159,6 +161,7 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->N = 0;
     c->next_unit = c->n_units = c->n_ls_units = 0;
     c->pinned = nullptr;
+    c->prof_on = false;
     c->x = nullptr;
     c->w = moe_weights{};
     *out = c;
@@ -168,6 +171,8 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
 int32_t moe_destroy(moe_ctx *ctx) {
     if (!ctx) return fail(MOE_E_ARG, "moe_destroy: null context");
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    for (auto &sp : ctx->prof.spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (auto e : ctx->prof.pool) (void)hipEventDestroy(e);
     delete ctx;
     return MOE_OK;
 }
@@ -283,12 +288,14 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
         a.out = at<float>(ctx, ctx->lay.out);
         a.H = ctx->cfg.H; a.F = ctx->cfg.F; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
         a.u0 = u0; a.nu = nu;
-        a.max_rows = 0; a.has_small = a.has_large = false;
+        a.max_rows = a.max_rows_small = 0; a.has_small = a.has_large = false;
         for (uint32_t u = u0; u < u0 + nu; ++u) {
             const int r = ctx->units[u].rows;
             if (r > a.max_rows) a.max_rows = r;
-            if (r <= qmoe::kSmallUnitRows) a.has_small = true; else a.has_large = true;
+            if (r <= qmoe::kSmallUnitRows) { a.has_small = true; if (r > a.max_rows_small) a.max_rows_small = r; }
+            else a.has_large = true;
         }
+        a.prof = ctx->prof_on ? &ctx->prof : nullptr;
         hipError_t e = qmoe::launch_experts(a, (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "moe_expert_run: launch");
     }
@@ -342,6 +349,29 @@ int32_t moe_get(moe_ctx *ctx, int32_t what, const void **dev_ptr, size_t *bytes)
     }
     *dev_ptr = ctx->ws + off;
     *bytes = sz;
+    return MOE_OK;
+}
+
+int32_t moe_profile(moe_ctx *ctx, int32_t enable) {
+    if (!ctx) return fail(MOE_E_ARG, "moe_profile: null context");
+    ctx->prof_on = enable != 0;
+    return MOE_OK;
+}
+
+int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches) {
+    if (!ctx || !ms || !launches) return fail(MOE_E_ARG, "moe_profile_read: null argument");
+    for (int i = 0; i < MOE_PROF_KINDS; ++i) { ms[i] = 0.f; launches[i] = 0; }
+    for (auto &sp : ctx->prof.spans) {
+        hipError_t e = hipEventSynchronize(sp.b);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, sp.a, sp.b);
+        if (e != hipSuccess) return hip_fail(e, "moe_profile_read");
+        ms[sp.kind] += t;
+        launches[sp.kind] += 1;
+        ctx->prof.pool.push_back(sp.a);
+        ctx->prof.pool.push_back(sp.b);
+    }
+    ctx->prof.spans.clear();
     return MOE_OK;
 }
 

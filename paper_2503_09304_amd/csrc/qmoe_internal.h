@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "qmoe.h"
 
 namespace qmoe {
@@ -17,7 +19,7 @@ constexpr int kMaxChunkRows = 256;
 // Units with at most this many rows take the K-split down-projection (more workgroups for the
 // weight-streaming shapes).  A property of the unit alone, so a unit's arithmetic never depends
 // on which other units share its launch.
-constexpr int kSmallUnitRows = 64;
+constexpr int kSmallUnitRows = 128;
 
 struct RouteArgs {
     const void *x;
@@ -48,6 +50,16 @@ struct PermuteArgs {
 };
 hipError_t launch_permute(const PermuteArgs &a, hipStream_t s);
 
+// Optional event bracketing of the expert launches (benchmarks only).
+struct Profiler {
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;        // recorded since the last read
+    std::vector<hipEvent_t> pool;   // events free for reuse
+    hipEvent_t get();
+    void begin(int kind, hipStream_t s);
+    void end(hipStream_t s);
+};
+
 struct ExpertArgs {
     const void *x;
     const void *W1, *W3, *W2;
@@ -58,7 +70,9 @@ struct ExpertArgs {
     int H, F, k, dtype;
     uint32_t u0, nu;        // units [u0, u0+nu)
     int max_rows;           // largest rows among those units (host copy of the list)
+    int max_rows_small;     // largest rows among the units with rows <= kSmallUnitRows
     bool has_small, has_large;  // unit classes present (rows <= / > kSmallUnitRows)
+    Profiler *prof;             // nullptr unless timing is on
 };
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
 
