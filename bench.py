@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy, the yardstick for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus must be 1")
@@ -82,6 +84,12 @@ def main() -> int:
         g.run()
         g.combine()
 
+    if args.calib_copy:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
