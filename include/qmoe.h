@@ -63,6 +63,12 @@ typedef struct {
     int32_t dtype;      /* moe_dtype                                                            */
     int32_t chunk_rows; /* C: most rows of one work unit, 1..256                                */
     int32_t max_tokens; /* capacity of the context, N <= max_tokens, max_tokens*k < 2^31        */
+    int32_t down_ksplit; /* K-split of the down projection: 0 = choose from the configuration, 1 = none,
+                            4 = four K quarters added in a fixed order (bf16, F % 256 == 0 only).
+                            0 picks 4 when F % 256 == 0 and max_tokens*k <= 256*E (weight-streaming
+                            shapes, where the split supplies the parallelism), else 1.  Part of the
+                            configuration, never of a launch: results of one context do not depend on it
+                            changing, because it cannot change.                                          */
 } moe_config;
 
 typedef struct {
@@ -70,7 +76,16 @@ typedef struct {
     const void *W1; /* [device] gate_proj      [E,F,H] (H contiguous)                           */
     const void *W3; /* [device] up_proj        [E,F,H] (H contiguous)                           */
     const void *W2; /* [device] down_proj      [E,H,F] (F contiguous)                           */
+    int32_t layout; /* MOE_W_ROWMAJOR: the shapes above.  MOE_W_PACKED: written by moe_pack_weights */
 } moe_weights;
+
+/* Weight layouts.  MOE_W_PACKED (bf16 only) stores every expert matrix M [R,K] (R % 32 == 0,
+ * K % 16 == 0) as 1 KiB blocks in the order a wave's MFMA B operand consumes them, so that a wave
+ * streams its weight rows with fully contiguous loads:
+ *     element (r, k)  ->  (((r/32) * (K/16) + k/16) * 64 + (r%32) + 32*((k%16)/8)) * 8 + k%8
+ * per expert, experts back to back (same total size as row-major); Wg is stored transposed and
+ * padded: [ceil16(E), H], rows >= E zero. */
+enum { MOE_W_ROWMAJOR = 0, MOE_W_PACKED = 1 };
 
 /* Where a layer-batch stands in its work-unit list.  A plain value: keeping a copy of it (and the
  * context's workspace) is all a preempted batch needs in order to resume. */
@@ -115,6 +130,13 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
 
 /* Frees the host object (and its pinned buffer).  Does not wait for enqueued work. */
 int32_t moe_destroy(moe_ctx *ctx);
+
+/* One-time re-layout of the weights at model load (outside any timed region).  src: row-major
+ * weights (layout MOE_W_ROWMAJOR).  dst: caller-allocated [device] buffers, W1/W3/W2 of the same
+ * sizes as the sources, Wg of ceil16(E)*H elements; on success dst->layout is set to MOE_W_PACKED
+ * and dst can be passed wherever weights are expected.  Results are bit-identical for both
+ * layouts.  bf16 only (MOE_E_ARG for MOE_F32).  Enqueues on `stream` and returns. */
+int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weights *dst, void *stream);
 
 /* Router (Sec. 2.1: "a router that assigns each token to the most relevant experts"; Sec. 2.2).
  *   logits[n,e] = sum_h x[n,h]*Wg[h,e] + logit_bias[e]      (fp32 accumulation)
@@ -173,7 +195,7 @@ int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_un
  * and kept by the context); moe_profile(ctx, 0) turns that off.  moe_profile_read waits for the
  * recorded events, adds up elapsed milliseconds and launch counts per kernel kind since the last
  * read into ms / launches ([host], MOE_PROF_KINDS entries each) and forgets them. */
-enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN_SMALL = 1, MOE_PROF_DOWN_LARGE = 2, MOE_PROF_KINDS = 3 };
+enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2, MOE_PROF_KINDS = 3 };
 int32_t moe_profile(moe_ctx *ctx, int32_t enable);
 int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches);
 

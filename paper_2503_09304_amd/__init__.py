@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     MOE_E_WORKSPACE,
     MOE_F32,
     MOE_OK,
+    MOE_W_PACKED,
+    MOE_W_ROWMAJOR,
     UINT32_MAX,
     Context,
     MoeConfig,
@@ -26,6 +28,7 @@ from .binding import (  # noqa: F401
     lib,
     lib_path,
     moe_last_error,
+    moe_pack_weights,
     moe_plan_units,
     moe_workspace_bytes,
 )

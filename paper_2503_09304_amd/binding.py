@@ -15,6 +15,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_OK, MOE_DONE = 0, 1
 MOE_E_ARG, MOE_E_STATE, MOE_E_INCOMPLETE, MOE_E_WORKSPACE, MOE_E_HIP = -1, -2, -3, -4, -5
 MOE_CLASS_LS, MOE_CLASS_BE, MOE_CLASS_ALL = 1, 2, 3
+MOE_W_ROWMAJOR, MOE_W_PACKED = 0, 1
 UINT32_MAX = 0xFFFFFFFF
 
 GET = {"logits": 0, "topk_idx": 1, "topk_w": 2, "counts": 3, "offsets": 4, "perm": 5, "inv": 6,
@@ -23,11 +24,13 @@ GET = {"logits": 0, "topk_idx": 1, "topk_w": 2, "counts": 3, "offsets": 4, "perm
 
 class MoeConfig(C.Structure):
     _fields_ = [("E", C.c_int32), ("k", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
-                ("dtype", C.c_int32), ("chunk_rows", C.c_int32), ("max_tokens", C.c_int32)]
+                ("dtype", C.c_int32), ("chunk_rows", C.c_int32), ("max_tokens", C.c_int32),
+                ("down_ksplit", C.c_int32)]
 
 
 class MoeWeights(C.Structure):
-    _fields_ = [("Wg", C.c_void_p), ("W1", C.c_void_p), ("W3", C.c_void_p), ("W2", C.c_void_p)]
+    _fields_ = [("Wg", C.c_void_p), ("W1", C.c_void_p), ("W3", C.c_void_p), ("W2", C.c_void_p),
+                ("layout", C.c_int32)]
 
 
 class MoeCursor(C.Structure):
@@ -72,9 +75,10 @@ def lib():
         L.moe_units.argtypes = [C.c_void_p, C.POINTER(MoeUnit), C.c_uint32, C.POINTER(C.c_uint32)]
         L.moe_plan_units.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(MoeUnit), C.c_uint32,
                                      C.POINTER(C.c_uint32)]
+        L.moe_pack_weights.argtypes = [C.POINTER(MoeConfig), C.POINTER(MoeWeights), C.POINTER(MoeWeights), C.c_void_p]
         L.moe_profile.argtypes = [C.c_void_p, C.c_int32]
         L.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
-        for f in ("moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
+        for f in ("moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
                   "moe_get", "moe_units", "moe_plan_units"):
             getattr(L, f).restype = C.c_int32
         _lib = L
@@ -109,6 +113,12 @@ def moe_plan_units(cnt, E: int, chunk_rows: int):
     return [(u.expert, u.cls, u.row0, u.rows) for u in out[: n.value]]
 
 
+def moe_pack_weights(cfg: MoeConfig, src: MoeWeights, dst: MoeWeights) -> MoeWeights:
+    """Re-layout row-major weights into dst's buffers (MOE_W_PACKED); returns dst."""
+    _check(lib().moe_pack_weights(C.byref(cfg), C.byref(src), C.byref(dst), _stream()))
+    return dst
+
+
 def _ptr(t) -> Optional[int]:
     return None if t is None else int(t.data_ptr())
 
@@ -122,9 +132,9 @@ class Context:
     """One in-flight layer-batch: the opaque moe_ctx plus the torch tensor that backs its workspace.
     Methods are the C calls with tensors in place of pointers."""
 
-    def __init__(self, E, k, H, F, dtype, chunk_rows, max_tokens, device="cuda:0"):
+    def __init__(self, E, k, H, F, dtype, chunk_rows, max_tokens, device="cuda:0", down_ksplit=0):
         import torch
-        self.cfg = MoeConfig(E, k, H, F, dtype, chunk_rows, max_tokens)
+        self.cfg = MoeConfig(E, k, H, F, dtype, chunk_rows, max_tokens, down_ksplit)
         self.nbytes = moe_workspace_bytes(self.cfg)
         self.ws = torch.empty(self.nbytes, dtype=torch.uint8, device=device)
         assert self.ws.data_ptr() % 256 == 0
@@ -147,8 +157,8 @@ class Context:
             pass
 
     @staticmethod
-    def weights(Wg, W1, W3, W2) -> MoeWeights:
-        return MoeWeights(_ptr(Wg), _ptr(W1), _ptr(W3), _ptr(W2))
+    def weights(Wg, W1, W3, W2, layout: int = MOE_W_ROWMAJOR) -> MoeWeights:
+        return MoeWeights(_ptr(Wg), _ptr(W1), _ptr(W3), _ptr(W2), layout)
 
     def route(self, x, w: MoeWeights, bias=None, n_tokens=None):
         n = x.shape[0] if n_tokens is None else n_tokens
@@ -175,7 +185,7 @@ class Context:
         ms = (C.c_float * 3)()
         n = (C.c_uint32 * 3)()
         _check(lib().moe_profile_read(self.h, ms, n))
-        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(("gate_up", "down_small", "down_large"))}
+        return {name: (float(ms[i]), int(n[i])) for i, name in enumerate(("gate_up", "down", "down_reduce"))}
 
     def units(self):
         n = C.c_uint32(0)

@@ -6,27 +6,32 @@
 // in fp32.  A workgroup has 4 waves.  Each wave owns 64 weight rows (gate-up: 32 rows of W1 and the
 // same 32 of W3, so the gate and up value of one (token, f) meet in one lane and register) and every
 // token tile of the unit.  No two waves use the same weight fragment, so weights go straight from
-// global memory into MFMA operand registers; only the token tile (gathered x rows, or act rows),
-// which all 4 waves share, is staged in LDS, double-buffered, its 16-byte slots XOR-swizzled by
-// row so that the 32 rows read by one ds_read_b128 fall into distinct banks.
+// global memory into MFMA operand registers (with the packed layout every wave load is one
+// contiguous KiB); only the token tile (gathered x rows, or act rows), which all 4 waves share, is
+// staged in LDS, double-buffered, its 16-byte slots XOR-swizzled by row so that the 32 rows read
+// by one ds_read_b128 fall into distinct banks.
 //
-// Pipeline of one K-iteration (64 k): write the token tile for iteration it+1 into the other LDS
-// stage, issue the global loads of the token tile for it+2 and of the weight fragments for it+2
-// (three register sets rotate), run the MFMAs of iteration it, one barrier.  Vector loads complete
-// in issue order, so this keeps two iterations of weights (16 KB per wave) in flight.
-// Loads are unconditional (row and iteration indices are clamped instead) so that the wait
-// counters stay exact.
+// Pipeline of one K-iteration (64 k), prefetch distance D: issue the global loads of the token
+// pieces and weight fragments for it+D (register rings of D+1 sets), run the MFMAs of iteration it,
+// write the token tile for it+1 into the other LDS stage, one barrier.  Vector loads complete in
+// issue order, so the waits leave about D iterations of weight loads (8 KB per wave each) in flight.  Loads are unconditional (row and iteration indices are
+// clamped instead) so that the wait counters stay exact.
 //
-// Shapes bound by weight streaming need more workgroups than output tiles exist in the down
-// projection: there (units of at most kSmallUnitRows rows) the 4 waves split K into 4 contiguous
-// quarters and add their partial tiles through LDS in wave order.
+// Down projection with K-split (a property of the context's configuration: weight-streaming shapes
+// have too few output tiles to fill the chip): K is cut into 4 contiguous quarters, each computed by
+// its own workgroup into a partial plane; a second kernel adds the planes in the fixed order
+// ((p0+p1)+p2)+p3.
+//
+// A launch works on row segments: a unit, or several row-adjacent units of one expert merged by the
+// host (the LS and BE part of an expert's queue), so that one pass over the weights serves them.
 //
 // Determinism.  Each output element is one chain of MFMA accumulations over K in ascending order
-// (K-split: 4 chains added in a fixed order).  Which variant a unit takes depends on the unit's own
-// row count and the configuration only, and tiles never mix units, so results are bit-identical
-// however the unit list is split into launches.
+// (K-split: 4 chains added in a fixed order), the same for every row of the context: it depends on
+// neither the tile a row sits in, nor the rows that share it, nor the weight layout.  Results are
+// therefore bit-identical however the unit list is split into launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -37,6 +42,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
@@ -52,45 +58,66 @@ __device__ __forceinline__ void static_for(F &&f) {
     static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
 }
 
-template <int T, bool GATEUP, int WK>
-__device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, const int ct, char *lds) {
-    constexpr int WN = 4 / WK;
+// Launch-local arguments of the bf16 kernels.
+struct BArgs {
+    KArgs k;
+    int ksplit;          // 1, or 4: K quarters, one workgroup each, partial planes in k.dst
+    long plane;          // elements between partial planes
+    int nseg;            // > 0: work on seg[0..nseg); 0: on units[u0 .. u0+nu) of the device list
+    Seg seg[kMaxSegs];
+};
+
+// One (unit, column tile, K range) on a workgroup.
+template <int T, bool GATEUP, bool PACKED, int D>
+__device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, const int ct, const int kq, const int ksplit,
+                                            const long plane, char *lds) {
     constexpr int ROWS = T * 32;
-    constexpr int STAGE = WK * ROWS * 128;  // bytes of one LDS stage: 64 bf16 per row
-    constexpr int CPW = GATEUP ? 32 : 64;   // output columns per wave
+    constexpr int STAGE = ROWS * 128;      // bytes of one LDS stage: 64 bf16 per row
+    constexpr int CPW = GATEUP ? 32 : 64;  // output columns per wave
     const int rows = un.rows;
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-    const int wn = w % WN, wk = w / WN;
     const int lr = l & 31, lh = l >> 5;
-    const int Kg = p.K / WK;
+    const int Kg = p.K / ksplit;           // this workgroup's K range: [kq*Kg, (kq+1)*Kg)
     const int iters = Kg / 64;
-    const int col_base = ct * (WN * CPW) + wn * CPW;
+    const int col_base = ct * (4 * CPW) + w * CPW;
 
     // ---- weight rows of this lane (B operand) ----
+    // Row-major: lane = (row l%32, k-half l/32), 16 elements per k-step, 64 per iteration.
+    // Packed: the wave's 1 KiB block of k-step s of row tile nt starts at (nt*(K/16)+s)*512.
+    constexpr int BKS = PACKED ? 512 : 16;   // elements between k-steps
+    constexpr int BIT = PACKED ? 2048 : 64;  // elements between iterations
     const uint16_t *bptr[2];
     {
         const uint16_t *b0 = (const uint16_t *)p.b0 + (long)un.expert * p.b_estride;
-        if (GATEUP) {
-            const uint16_t *b1 = (const uint16_t *)p.b1 + (long)un.expert * p.b_estride;
-            const int c = min(col_base + lr, p.ncols - 1);
-            bptr[0] = b0 + (long)c * p.K + wk * Kg + lh * 8;
-            bptr[1] = b1 + (long)c * p.K + wk * Kg + lh * 8;
+        const uint16_t *b1 = GATEUP ? (const uint16_t *)p.b1 + (long)un.expert * p.b_estride : b0;
+        if (PACKED) {
+            const int ntiles = p.ncols >> 5;
+            const long tile_elems = (long)p.K * 32;
+            const long koff = (long)kq * (Kg / 16) * 512 + l * 8;
+            const int nt0 = min(col_base >> 5, ntiles - 1);
+            const int nt1 = GATEUP ? nt0 : min((col_base >> 5) + 1, ntiles - 1);
+            bptr[0] = b0 + nt0 * tile_elems + koff;
+            bptr[1] = b1 + nt1 * tile_elems + koff;
         } else {
-            const int c0 = min(col_base + lr, p.ncols - 1), c1 = min(col_base + 32 + lr, p.ncols - 1);
-            bptr[0] = b0 + (long)c0 * p.K + wk * Kg + lh * 8;
-            bptr[1] = b0 + (long)c1 * p.K + wk * Kg + lh * 8;
+            const int c0 = min(col_base + lr, p.ncols - 1);
+            const int c1 = GATEUP ? c0 : min(col_base + 32 + lr, p.ncols - 1);
+            bptr[0] = b0 + (long)c0 * p.K + kq * Kg + lh * 8;
+            bptr[1] = b1 + (long)c1 * p.K + kq * Kg + lh * 8;
         }
     }
     // ---- token rows this thread stages into LDS (A operand): row tid/8 + 32*j, slot tid%8 ----
     const int srow = tid >> 3, sslot = tid & 7;
-    const uint16_t *arow[T];
+    // Addressed as a wave-uniform 64-bit base plus a 32-bit byte offset per row (the host checks
+    // that x and act stay below 4 GiB), which halves the registers the row table costs.
+    const char *abase = (const char *)p.a_src + ((long)kq * Kg + sslot * 8) * 2;
+    unsigned aoff[T];
     static_for<T>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         const int r = min(srow + 32 * j, rows - 1);
-        long src_row;
-        if (GATEUP) src_row = p.perm[un.row0 + r] / p.kdiv;
-        else src_row = un.row0 + r;
-        arow[j] = (const uint16_t *)p.a_src + src_row * p.lda + sslot * 8;
+        unsigned src_row;
+        if (GATEUP) src_row = (unsigned)(p.perm[un.row0 + r] / p.kdiv);
+        else src_row = (unsigned)(un.row0 + r);
+        aoff[j] = src_row * (unsigned)p.lda * 2u;
     });
 
     f32x16 acc[T][2];
@@ -100,21 +127,27 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         for (int r = 0; r < 16; ++r) { acc[t][0][r] = 0.f; acc[t][1][r] = 0.f; }
     });
 
-    u32x4 a_reg[WK * T];
-    bf16x8 b_reg[3 * 8];  // [set][k-step][n-tile]
+    // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
+    // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
+    constexpr int DA = D >= 3 ? D : 1;   // token pieces: same distance, or 1 where registers are scarce
+    constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
+    u32x4 a_reg[NA * T];
+    bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]
 
-    auto load_a = [&](int it) {
+    auto load_a = [&](int it, auto setc) {
+        constexpr int S = decltype(setc)::value;
         const int itc = min(it, iters - 1);
-        static_for<WK * T>([&](auto ic) {
-            constexpr int g = decltype(ic)::value / T, j = decltype(ic)::value % T;
-            a_reg[g * T + j] = *reinterpret_cast<const u32x4 *>(arow[j] + g * Kg + itc * 64);
+        static_for<T>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            a_reg[S * T + j] = *reinterpret_cast<const u32x4 *>(abase + (aoff[j] + (unsigned)itc * 128u));
         });
     };
-    auto store_a = [&](int stage) {
-        static_for<WK * T>([&](auto ic) {
-            constexpr int g = decltype(ic)::value / T, j = decltype(ic)::value % T;
+    auto store_a = [&](int stage, auto setc) {
+        constexpr int S = decltype(setc)::value;
+        static_for<T>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
             const int r = srow + 32 * j;
-            *reinterpret_cast<u32x4 *>(lds + stage * STAGE + ((g * ROWS + r) * 8 + (sslot ^ (r & 7))) * 16) = a_reg[g * T + j];
+            *reinterpret_cast<u32x4 *>(lds + stage * STAGE + (r * 8 + (sslot ^ (r & 7))) * 16) = a_reg[S * T + j];
         });
     };
     auto load_b = [&](int it, auto setc) {
@@ -122,71 +155,71 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         const int itc = min(it, iters - 1);
         static_for<4>([&](auto kc) {
             constexpr int ks = decltype(kc)::value;
-            b_reg[S * 8 + ks * 2 + 0] = *reinterpret_cast<const bf16x8 *>(bptr[0] + itc * 64 + ks * 16);
-            b_reg[S * 8 + ks * 2 + 1] = *reinterpret_cast<const bf16x8 *>(bptr[1] + itc * 64 + ks * 16);
+            b_reg[S * 8 + ks * 2 + 0] = *reinterpret_cast<const bf16x8 *>(bptr[0] + (long)itc * BIT + ks * BKS);
+            b_reg[S * 8 + ks * 2 + 1] = *reinterpret_cast<const bf16x8 *>(bptr[1] + (long)itc * BIT + ks * BKS);
+        });
+    };
+    // MFMAs of one iteration.  Token fragments are read from LDS one half-step (HT tiles of one
+    // k-step) ahead of the MFMAs that use them.
+    constexpr int HT = T >= 8 ? 4 : T, NH = T / HT, STEPS = 4 * NH;
+    bf16x8 af[2 * HT];
+    auto read_af = [&](int stage, auto hsc) {
+        constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;
+        static_for<HT>([&](auto tc) {
+            constexpr int t = h * HT + decltype(tc)::value;
+            const int r = t * 32 + lr;
+            const int slot = (ks * 2 + lh) ^ (r & 7);
+            af[(hs & 1) * HT + decltype(tc)::value] = *reinterpret_cast<const bf16x8 *>(lds + stage * STAGE + (r * 8 + slot) * 16);
         });
     };
     auto mfma_tile = [&](int stage, auto setc) {
         constexpr int S = decltype(setc)::value;
-        static_for<4 * T>([&](auto ic) {
-            constexpr int ks = decltype(ic)::value / T, t = decltype(ic)::value % T;
-            const int r = t * 32 + lr;
-            const int slot = (ks * 2 + lh) ^ (r & 7);
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(lds + stage * STAGE + ((wk * ROWS + r) * 8 + slot) * 16);
-            acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b_reg[S * 8 + ks * 2 + 0], acc[t][0], 0, 0, 0);
-            acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b_reg[S * 8 + ks * 2 + 1], acc[t][1], 0, 0, 0);
+        read_af(stage, std::integral_constant<int, 0>{});
+        static_for<STEPS>([&](auto hsc) {
+            constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;
+            if constexpr (hs + 1 < STEPS) read_af(stage, std::integral_constant<int, hs + 1>{});
+            static_for<HT>([&](auto tc) {
+                constexpr int t = h * HT + decltype(tc)::value;
+                const bf16x8 a = af[(hs & 1) * HT + decltype(tc)::value];
+                acc[t][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b_reg[S * 8 + ks * 2 + 0], acc[t][0], 0, 0, 0);
+                acc[t][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b_reg[S * 8 + ks * 2 + 1], acc[t][1], 0, 0, 0);
+            });
         });
     };
-    auto body = [&](int it, auto sc) {
-        constexpr int S = decltype(sc)::value;
-        store_a((it + 1) & 1);
-        load_a(it + 2);
-        load_b(it + 2, std::integral_constant<int, (S + 2) % 3>{});
-        mfma_tile(it & 1, sc);
+    // Iteration `it`, position i = it mod U in the unrolled loop: request the operands of it+D, run
+    // the MFMAs of it, then move the token pieces of it+1 (requested earlier) into the
+    // other LDS stage.  Loads complete in issue order, so neither wait disturbs the iterations of
+    // weight loads issued after the data waited for.  The scheduling barriers keep the compiler
+    // from moving loads across the phases, which would change what the waits cover.
+    auto body = [&](int it, auto ic) {
+        constexpr int i = decltype(ic)::value;
+        load_a(it + DA, std::integral_constant<int, (i + DA) % NA>{});
+        load_b(it + D, std::integral_constant<int, (i + D) % NB>{});
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_tile(it & 1, std::integral_constant<int, i % NB>{});
+        __builtin_amdgcn_sched_barrier(0);
+        store_a((it + 1) & 1, std::integral_constant<int, (i + 1) % NA>{});
         __syncthreads();
     };
 
-    load_a(0);
+    // prologue: operands of iterations 0 .. D-1; tile 0 into LDS stage 0
+    load_a(0, std::integral_constant<int, 0>{});
     load_b(0, std::integral_constant<int, 0>{});
-    load_b(1, std::integral_constant<int, 1>{});
-    store_a(0);
-    load_a(1);
+    store_a(0, std::integral_constant<int, 0>{});
+    static_for<D - 1>([&](auto ic) {
+        constexpr int j = decltype(ic)::value + 1;
+        if constexpr (j < DA) load_a(j, std::integral_constant<int, j % NA>{});
+        load_b(j, std::integral_constant<int, j % NB>{});
+    });
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     int it = 0;
-    for (; it + 3 <= iters; it += 3) {
-        body(it, std::integral_constant<int, 0>{});
-        body(it + 1, std::integral_constant<int, 1>{});
-        body(it + 2, std::integral_constant<int, 2>{});
+    for (; it + U <= iters; it += U) {
+        static_for<U>([&](auto ic) { body(it + decltype(ic)::value, ic); });
     }
-    if (it < iters) {
-        body(it, std::integral_constant<int, 0>{});
-        if (it + 1 < iters) body(it + 1, std::integral_constant<int, 1>{});
-    }
-
-    // ---- K-split: add the 4 partial tiles in wave order (LDS stages are free after the last barrier)
-    if (WK > 1) {
-        float *red = reinterpret_cast<float *>(lds);
-        if (wk > 0) {
-            static_for<2 * T>([&](auto ic) {
-                constexpr int t = decltype(ic)::value / 2, n = decltype(ic)::value % 2;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) red[(((wk - 1) * T + t) * 2 + n) * 1024 + r * 64 + l] = acc[t][n][r];
-            });
-        }
-        __syncthreads();
-        if (wk > 0) return;
-        static_for<2 * T>([&](auto ic) {
-            constexpr int t = decltype(ic)::value / 2, n = decltype(ic)::value % 2;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = acc[t][n][r];
-                v += red[((0 * T + t) * 2 + n) * 1024 + r * 64 + l];
-                v += red[((1 * T + t) * 2 + n) * 1024 + r * 64 + l];
-                v += red[((2 * T + t) * 2 + n) * 1024 + r * 64 + l];
-                acc[t][n][r] = v;
-            }
-        });
-    }
+    static_for<U - 1>([&](auto ic) {
+        if (it + decltype(ic)::value < iters) body(it + decltype(ic)::value, ic);
+    });
 
     // ---- epilogue.  D register r of lane l: token 8*(r/4) + 4*(l/32) + r%4, weight row l%32 ----
     static_for<T>([&](auto tc) {
@@ -203,7 +236,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
                     }
                 } else {
                     const int h0 = col_base + lr, h1 = h0 + 32;
-                    float *o = (float *)p.dst + (long)(un.row0 + i) * p.ldd;
+                    float *o = (float *)p.dst + kq * plane + (long)(un.row0 + i) * p.ldd;
                     if (h0 < p.ncols) o[h0] = acc[t][0][r];
                     if (h1 < p.ncols) o[h1] = acc[t][1][r];
                 }
@@ -212,58 +245,144 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     });
 }
 
+// Workgroup id -> (unit, column tile, K quarter).  The hardware deals consecutive workgroup ids
+// round-robin to the 8 XCDs (each with its own L2).  Work is cut into packets of 4 consecutive
+// units (in launch order) x 8 consecutive column tiles = 32 workgroups = one XCD's 32 CUs: the 4
+// token tiles are each shared by 8 workgroups and, when the units belong to one expert (chunks of
+// a long queue, or its LS and BE part), the 8 weight tiles by up to 4.  Packet q goes to XCD q % 8;
+// the workgroups of a packet get ids 8 apart.  With a K-split the column-tile axis is
+// (quarter, tile), quarter slowest, so a packet stays inside one quarter.
+__device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct, int &kq) {
+    const int w = blockIdx.x;
+    const int x = w & 7, j = w >> 3;
+    const int packet = (j >> 5) * 8 + x, within = j & 31;
+    const int n = b.nseg > 0 ? b.nseg : b.k.nu;
+    const int ugroups = (n + 3) >> 2;
+    const int ctb = packet / ugroups, ug = packet - ctb * ugroups;
+    const int pos = ug * 4 + (within >> 3);
+    const int cq = ctb * 8 + (within & 7);
+    if (pos >= n || cq >= b.k.col_tiles * b.ksplit) return false;
+    if (b.nseg > 0) {
+        const Seg g = b.seg[pos];
+        un.expert = g.expert; un.cls = 0; un.row0 = (int)g.row0; un.rows = g.rows;
+    } else {
+        un = b.k.units[b.k.u0 + pos];
+    }
+    kq = cq / b.k.col_tiles;
+    ct = cq - kq * b.k.col_tiles;
+    return true;
+}
+
 // TCAP: largest number of 32-token tiles a unit of this launch may have (1, 2, 4 or 8).  A
 // workgroup takes the smallest fully unrolled variant that covers its unit.
-template <int TCAP, bool GATEUP, int WK>
-__global__ __launch_bounds__(256) void expert_bf16(const KArgs p) {
-    __shared__ __attribute__((aligned(16))) char lds[2 * WK * TCAP * 32 * 128];
-    const int ui = blockIdx.x / p.col_tiles, ct = blockIdx.x - ui * p.col_tiles;
-    const moe_unit un = p.units[p.u0 + ui];
-    if (p.cls_filter == 1 && un.rows > kSmallUnitRows) return;
-    if (p.cls_filter == 2 && un.rows <= kSmallUnitRows) return;
+template <int TCAP, bool GATEUP, bool PACKED>
+__global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
+    __shared__ __attribute__((aligned(16))) char lds[2 * TCAP * 32 * 128];
+    int ct, kq;
+    moe_unit un;
+    if (!map_block(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
-    if (TCAP >= 8 && t_cnt > 4) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WK>(p, un, ct, lds);
-    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, WK>(p, un, ct, lds);
-    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, WK>(p, un, ct, lds);
-    else expert_tile<1, GATEUP, WK>(p, un, ct, lds);
+    // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
+    if (TCAP >= 8 && t_cnt > 4) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else expert_tile<1, GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
 }
 
-template <int TCAP, bool GATEUP, int WK>
-void launch1(const KArgs &k, unsigned nu, hipStream_t s) {
-    hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, WK>), dim3(nu * (unsigned)k.col_tiles), dim3(256), 0, s, k);
+// out[r,:] = ((p0 + p1) + p2) + p3 for the rows of the launch.
+__global__ __launch_bounds__(256) void reduce_planes(const BArgs b, const float *__restrict__ part, float *__restrict__ out, int H) {
+    const long plane = b.plane;
+    moe_unit un;
+    if (b.nseg > 0) {
+        const Seg g = b.seg[blockIdx.y];
+        un.row0 = (int)g.row0; un.rows = g.rows;
+    } else {
+        un = b.k.units[b.k.u0 + blockIdx.y];
+    }
+    const int per_row = H >> 2;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < (long)un.rows * per_row; i += (long)gridDim.x * 256) {
+        const long off = ((long)un.row0 * H) + i * 4;
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(part + off);
+        const f32x4 p1 = *reinterpret_cast<const f32x4 *>(part + plane + off);
+        const f32x4 p2 = *reinterpret_cast<const f32x4 *>(part + 2 * plane + off);
+        const f32x4 p3 = *reinterpret_cast<const f32x4 *>(part + 3 * plane + off);
+        f32x4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = ((a[q] + p1[q]) + p2[q]) + p3[q];
+        *reinterpret_cast<f32x4 *>(out + off) = v;
+    }
 }
 
-template <bool GATEUP, int WK>
-void launch_t(int tiles, const KArgs &k, unsigned nu, hipStream_t s) {
-    if (tiles <= 1) launch1<1, GATEUP, WK>(k, nu, s);
-    else if (tiles <= 2) launch1<2, GATEUP, WK>(k, nu, s);
-    else if (tiles <= 4 || WK > 1) launch1<4, GATEUP, WK>(k, nu, s);   // K-split serves units of <= 128 rows only
-    else if constexpr (WK == 1) launch1<8, GATEUP, WK>(k, nu, s);
+// Re-layout of [E][R][K] row-major bf16 into the packed block order: one thread per 16-byte piece.
+__global__ __launch_bounds__(256) void pack_weights_bf16(const uint4 *__restrict__ src, uint4 *__restrict__ dst, long pieces,
+                                                         int R, int K) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;   // destination piece index
+    if (i >= pieces) return;
+    const long per_expert = (long)R * K / 8;
+    const long e = i / per_expert, q = i - e * per_expert;
+    const int lane = (int)(q & 63);
+    const long blk = q >> 6;                                // nt * (K/16) + kstep
+    const int ksteps = K / 16;
+    const long nt = blk / ksteps;
+    const int ks = (int)(blk - nt * ksteps);
+    const long r = nt * 32 + (lane & 31);
+    const int k = ks * 16 + (lane >> 5) * 8;
+    dst[i] = src[(e * R + r) * (K / 8) + k / 8];
+}
+
+template <int TCAP, bool GATEUP>
+void launch1(const BArgs &b, bool packed, hipStream_t s) {
+    const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : (unsigned)b.k.nu;
+    const unsigned ugroups = (n + 3) / 4, ctb = (b.k.col_tiles * b.ksplit + 7) / 8;
+    const unsigned packets = ugroups * ctb;
+    const unsigned grid = (packets + 7) / 8 * 8 * 32;
+    if (packed) hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, true>), dim3(grid), dim3(256), 0, s, b);
+    else hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, false>), dim3(grid), dim3(256), 0, s, b);
+}
+
+template <bool GATEUP>
+void launch_t(int tiles, const BArgs &b, bool packed, hipStream_t s) {
+    if (tiles <= 1) launch1<1, GATEUP>(b, packed, s);
+    else if (tiles <= 2) launch1<2, GATEUP>(b, packed, s);
+    else if (tiles <= 4) launch1<4, GATEUP>(b, packed, s);
+    else launch1<8, GATEUP>(b, packed, s);
 }
 
 }  // namespace
 
+hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStream_t s) {
+    const long pieces = (long)E * R * K / 8;
+    hipLaunchKernelGGL(pack_weights_bf16, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const uint4 *)src,
+                       (uint4 *)dst, pieces, R, K);
+    return hipGetLastError();
+}
+
 void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &dn_in, hipStream_t s) {
-    KArgs gu = gu_in;
-    gu.col_tiles = (a.F + 127) / 128;
-    { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch_t<true, 1>((a.max_rows + 31) / 32, gu, a.nu, s); }
-    // Down projection.  Units of at most kSmallUnitRows rows split K over the 4 waves when F allows
-    // it: 4x the workgroups for the weight-streaming shapes.  The choice depends on the unit's row
-    // count and on F only, never on what else is in the launch.
-    const bool ksplit = (a.F % 256) == 0;
-    if (a.has_small) {
-        KArgs d = dn_in;
-        d.cls_filter = 1;
-        Scope sc(a.prof, MOE_PROF_DOWN_SMALL, s);
-        if (ksplit) { d.col_tiles = (a.H + 63) / 64; launch_t<false, 4>((a.max_rows_small + 31) / 32, d, a.nu, s); }
-        else { d.col_tiles = (a.H + 255) / 256; launch_t<false, 1>((a.max_rows_small + 31) / 32, d, a.nu, s); }
-    }
-    if (a.has_large) {
-        KArgs d = dn_in;
-        d.cls_filter = 2;
-        d.col_tiles = (a.H + 255) / 256;
-        Scope sc(a.prof, MOE_PROF_DOWN_LARGE, s);
-        launch_t<false, 1>((a.max_rows + 31) / 32, d, a.nu, s);
+    BArgs b{};
+    b.ksplit = 1;
+    b.plane = 0;
+    b.nseg = a.segs ? a.nseg : 0;
+    if (b.nseg > 0) std::copy(a.segs, a.segs + a.nseg, b.seg);
+    const int tiles = (a.max_rows + 31) / 32;
+    const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : a.nu;
+
+    b.k = gu_in;
+    b.k.col_tiles = (a.F + 127) / 128;
+    { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch_t<true>(tiles, b, a.packed, s); }
+
+    b.k = dn_in;
+    b.k.col_tiles = (a.H + 255) / 256;
+    if (a.ksplit == 4 && a.partial != nullptr) {
+        b.ksplit = 4;
+        b.plane = a.plane;
+        b.k.dst = a.partial;
+        { Scope sc(a.prof, MOE_PROF_DOWN, s); launch_t<false>(tiles, b, a.packed, s); }
+        const int per_seg = std::max(1, std::min(64, (a.max_rows * (a.H / 4) + 255) / 256));
+        Scope sc(a.prof, MOE_PROF_DOWN_REDUCE, s);
+        hipLaunchKernelGGL(reduce_planes, dim3(per_seg, n), dim3(256), 0, s, b, (const float *)a.partial, a.out, a.H);
+    } else {
+        Scope sc(a.prof, MOE_PROF_DOWN, s);
+        launch_t<false>(tiles, b, a.packed, s);
     }
 }
 

@@ -16,8 +16,8 @@ struct KArgs {
     long b_estride;         // elements per expert in b0/b1
     int lda, K, ncols, ldd, kdiv;
     unsigned u0;
+    int nu;                 // units in this launch
     int col_tiles;
-    int cls_filter;         // 0 = every unit, 1 = only rows <= kSmallUnitRows, 2 = only larger
 };
 
 struct Scope {

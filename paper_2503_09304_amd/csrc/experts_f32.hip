@@ -94,7 +94,7 @@ void launch_experts_f32(const ExpertArgs &a, const KArgs &gu_in, const KArgs &dn
     dn.col_tiles = (a.H + 63) / 64;
     { Scope sc(a.prof, MOE_PROF_GATE_UP, s);
       hipLaunchKernelGGL(expert_f32<true>, dim3(a.nu * row_tiles * gu.col_tiles), dim3(256), 0, s, gu, row_tiles); }
-    { Scope sc(a.prof, MOE_PROF_DOWN_LARGE, s);
+    { Scope sc(a.prof, MOE_PROF_DOWN, s);
       hipLaunchKernelGGL(expert_f32<false>, dim3(a.nu * row_tiles * dn.col_tiles), dim3(256), 0, s, dn, row_tiles); }
 }
 

@@ -5,6 +5,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -40,15 +41,29 @@ bool config_ok(const moe_config *c, const char **why) {
     if (c->dtype == MOE_BF16 && (c->H % 64 || c->F % 64)) { *why = "bf16 needs H and F multiples of 64"; return false; }
     if (c->chunk_rows < 1 || c->chunk_rows > qmoe::kMaxChunkRows) { *why = "chunk_rows out of range (1..256)"; return false; }
     if (c->max_tokens < 0) { *why = "max_tokens negative"; return false; }
+    if (c->down_ksplit != 0 && c->down_ksplit != 1 && c->down_ksplit != 4) { *why = "down_ksplit must be 0, 1 or 4"; return false; }
+    if (c->down_ksplit == 4 && (c->dtype != MOE_BF16 || c->F % 256)) { *why = "down_ksplit 4 needs bf16 and F a multiple of 256"; return false; }
     if ((int64_t)c->max_tokens * c->k >= (int64_t)1 << 31) { *why = "max_tokens*k must be below 2^31"; return false; }
+    if (c->dtype == MOE_BF16 && ((int64_t)c->max_tokens * c->H * 2 >= (int64_t)1 << 32 ||
+                                 (int64_t)c->max_tokens * c->k * c->F * 2 >= (int64_t)1 << 32)) {
+        *why = "bf16: x (max_tokens*H) and the activation (max_tokens*k*F) must each stay below 4 GiB";
+        return false;
+    }
     return true;
 }
 
 // Offsets of the workspace regions, computed the same way for sizing and for carving.
 struct Layout {
-    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, units, wgt, act, out, total;
+    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, units, wgt, act, out, partial, total;
+    bool has_partial;
     uint32_t max_units;
 };
+
+int down_ksplit(const moe_config &c) {
+    if (c.dtype != MOE_BF16 || c.F % 256) return 1;
+    if (c.down_ksplit) return c.down_ksplit;
+    return (int64_t)c.max_tokens * c.k <= (int64_t)256 * c.E ? 4 : 1;
+}
 
 Layout make_layout(const moe_config &c) {
     Layout L{};
@@ -73,6 +88,9 @@ Layout make_layout(const moe_config &c) {
     L.wgt = take(((E + 15) / 16 * 16) * (size_t)c.H * 2);
     L.act = take(A * (size_t)c.F * es);
     L.out = take(A * (size_t)c.H * 4);
+    // K-split down projection (bf16, F a multiple of 256): four partial planes shaped like `out`
+    L.has_partial = down_ksplit(c) == 4;
+    L.partial = L.has_partial ? take(4 * A * (size_t)c.H * 4) : 0;
     L.total = p ? p : kAlign;
     return L;
 }
@@ -142,6 +160,25 @@ int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_un
     return MOE_OK;
 }
 
+int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weights *dst, void *stream) {
+    const char *why;
+    if (!config_ok(cfg, &why)) return fail(MOE_E_ARG, "moe_pack_weights: %s", why);
+    if (cfg->dtype != MOE_BF16) return fail(MOE_E_ARG, "moe_pack_weights: bf16 only");
+    if (!src || !dst || !src->Wg || !src->W1 || !src->W3 || !src->W2 || !dst->Wg || !dst->W1 || !dst->W3 || !dst->W2)
+        return fail(MOE_E_ARG, "moe_pack_weights: null pointer");
+    if (src->layout != MOE_W_ROWMAJOR) return fail(MOE_E_ARG, "moe_pack_weights: source must be row-major");
+    if (src->W1 == dst->W1 || src->W3 == dst->W3 || src->W2 == dst->W2 || src->Wg == dst->Wg)
+        return fail(MOE_E_ARG, "moe_pack_weights: cannot pack in place");
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = qmoe::launch_pack(src->W1, const_cast<void *>(dst->W1), cfg->E, cfg->F, cfg->H, s);
+    if (e == hipSuccess) e = qmoe::launch_pack(src->W3, const_cast<void *>(dst->W3), cfg->E, cfg->F, cfg->H, s);
+    if (e == hipSuccess) e = qmoe::launch_pack(src->W2, const_cast<void *>(dst->W2), cfg->E, cfg->H, cfg->F, s);
+    if (e == hipSuccess) e = qmoe::launch_pack_gate(src->Wg, const_cast<void *>(dst->Wg), cfg->H, cfg->E, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_pack_weights: launch");
+    dst->layout = MOE_W_PACKED;
+    return MOE_OK;
+}
+
 int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_bytes, moe_ctx **out) {
     const char *why;
     if (!out) return fail(MOE_E_ARG, "moe_create: null out pointer");
@@ -183,6 +220,8 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens)
         return fail(MOE_E_ARG, "moe_route: n_tokens %d outside 0..%d", n_tokens, ctx->cfg.max_tokens);
     if (!w || !w->Wg || !w->W1 || !w->W3 || !w->W2) return fail(MOE_E_ARG, "moe_route: null weight pointer");
+    if (w->layout != MOE_W_ROWMAJOR && w->layout != MOE_W_PACKED) return fail(MOE_E_ARG, "moe_route: unknown weight layout %d", w->layout);
+    if (w->layout == MOE_W_PACKED && ctx->cfg.dtype != MOE_BF16) return fail(MOE_E_ARG, "moe_route: packed weights are bf16 only");
     if (n_tokens > 0 && !x) return fail(MOE_E_ARG, "moe_route: null x");
     if (!ctx->pinned) {
         hipError_t e = hipHostMalloc((void **)&ctx->pinned, (2 * (size_t)ctx->cfg.E + 1) * sizeof(int32_t), hipHostMallocDefault);
@@ -196,6 +235,7 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
         a.topk_idx = at<int32_t>(ctx, ctx->lay.topk_idx);
         a.topk_w = at<float>(ctx, ctx->lay.topk_w);
         a.N = n_tokens; a.H = ctx->cfg.H; a.E = ctx->cfg.E; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
+        a.packed = w->layout == MOE_W_PACKED;
         hipError_t e = qmoe::launch_route(a, (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "moe_route: launch");
     }
@@ -274,7 +314,7 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
         return fail(MOE_E_ARG, "moe_expert_run: cursor {%u,%u} is not this context's {%u,%u}", cursor->next_unit,
                     cursor->n_units, ctx->next_unit, ctx->n_units);
     if (!w || (ctx->N > 0 && !x)) return fail(MOE_E_ARG, "moe_expert_run: null x or weights");
-    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2)
+    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout)
         return fail(MOE_E_ARG, "moe_expert_run: x and weights must be the tensors given to moe_route");
     const uint32_t u0 = ctx->next_unit;
     const uint32_t left = ctx->n_units - u0;
@@ -288,14 +328,47 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
         a.out = at<float>(ctx, ctx->lay.out);
         a.H = ctx->cfg.H; a.F = ctx->cfg.F; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
         a.u0 = u0; a.nu = nu;
-        a.max_rows = a.max_rows_small = 0; a.has_small = a.has_large = false;
-        for (uint32_t u = u0; u < u0 + nu; ++u) {
-            const int r = ctx->units[u].rows;
-            if (r > a.max_rows) a.max_rows = r;
-            if (r <= qmoe::kSmallUnitRows) { a.has_small = true; if (r > a.max_rows_small) a.max_rows_small = r; }
-            else a.has_large = true;
-        }
         a.prof = ctx->prof_on ? &ctx->prof : nullptr;
+        a.packed = w->layout == MOE_W_PACKED;
+        a.ksplit = ctx->lay.has_partial ? 4 : 1;
+        a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
+        a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
+        // Row segments of this launch: units sorted by (expert, row), row-adjacent units of one
+        // expert (its LS part and the start of its BE part, or consecutive chunks) merged while they
+        // fit 256 rows, so that one pass over the expert's weights serves them all.  Which rows
+        // share a workgroup never changes what is computed for a row.
+        std::vector<qmoe::Seg> segs;
+        a.max_rows = 0;
+        if (ctx->cfg.dtype == MOE_BF16) {
+            std::vector<uint32_t> idx(nu);
+            for (uint32_t i = 0; i < nu; ++i) idx[i] = u0 + i;
+            const moe_unit *un = ctx->units.data();
+            std::stable_sort(idx.begin(), idx.end(), [un](uint32_t x, uint32_t y) {
+                if (un[x].expert != un[y].expert) return un[x].expert < un[y].expert;
+                return un[x].row0 < un[y].row0;
+            });
+            for (uint32_t i : idx) {
+                const moe_unit &u = un[i];
+                if (!segs.empty()) {
+                    qmoe::Seg &b = segs.back();
+                    if (b.expert == (uint16_t)u.expert && b.row0 + b.rows == (uint32_t)u.row0 && b.rows + u.rows <= 256) {
+                        b.rows = (uint16_t)(b.rows + u.rows);
+                        continue;
+                    }
+                }
+                segs.push_back(qmoe::Seg{(uint32_t)u.row0, (uint16_t)u.rows, (uint16_t)u.expert});
+            }
+            if (segs.size() > (size_t)qmoe::kMaxSegs) segs.clear();
+        }
+        if (!segs.empty()) {
+            for (const qmoe::Seg &g : segs) if (g.rows > a.max_rows) a.max_rows = g.rows;
+            a.segs = segs.data();
+            a.nseg = (int)segs.size();
+        } else {
+            for (uint32_t u = u0; u < u0 + nu; ++u) if (ctx->units[u].rows > a.max_rows) a.max_rows = ctx->units[u].rows;
+            a.segs = nullptr;
+            a.nseg = 0;
+        }
         hipError_t e = qmoe::launch_experts(a, (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "moe_expert_run: launch");
     }

@@ -16,10 +16,16 @@ constexpr int kMaxExperts = 256;  // 2*E bucket counters of a 16-wave workgroup 
 constexpr int kMaxTopK = 32;
 constexpr int kMaxChunkRows = 256;
 
-// Units with at most this many rows take the K-split down-projection (more workgroups for the
-// weight-streaming shapes).  A property of the unit alone, so a unit's arithmetic never depends
-// on which other units share its launch.
-constexpr int kSmallUnitRows = 128;
+// A launch of at most this many row segments carries them in its kernel arguments (and may merge
+// row-adjacent units of one expert into one segment); larger launches read the device unit list.
+constexpr int kMaxSegs = 256;
+
+// Rows [row0, row0+rows) of the sorted order, all of one expert: what one workgroup column works on.
+struct Seg {
+    uint32_t row0;
+    uint16_t rows;    // 1..256
+    uint16_t expert;
+};
 
 struct RouteArgs {
     const void *x;
@@ -30,6 +36,7 @@ struct RouteArgs {
     int32_t *topk_idx;
     float *topk_w;
     int N, H, E, k, dtype;
+    bool packed;  // Wg already transposed and padded ([E16][H])
 };
 hipError_t launch_route(const RouteArgs &a, hipStream_t s);
 
@@ -69,12 +76,20 @@ struct ExpertArgs {
     float *out;             // [A,H]
     int H, F, k, dtype;
     uint32_t u0, nu;        // units [u0, u0+nu)
-    int max_rows;           // largest rows among those units (host copy of the list)
-    int max_rows_small;     // largest rows among the units with rows <= kSmallUnitRows
-    bool has_small, has_large;  // unit classes present (rows <= / > kSmallUnitRows)
+    int max_rows;           // largest rows among the segments (or units) of the launch
     Profiler *prof;             // nullptr unless timing is on
+    bool packed;                // expert weights in the MFMA-ordered 1 KiB-block layout
+    const Seg *segs;            // host array [nseg] (nseg <= kMaxSegs), or nullptr: use the unit list
+    int nseg;
+    int ksplit;                 // 1 or 4 (down projection; fixed per context)
+    float *partial;             // [4][A][H] fp32 partial planes of the K-split down projection, or nullptr
+    long plane;                 // elements per plane
 };
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
+
+// Re-layout of one [E][R][K] bf16 tensor into the packed block order (see MOE_W_PACKED).
+hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStream_t s);
+hipError_t launch_pack_gate(const void *Wg, void *WgT, int H, int E, hipStream_t s);
 
 struct CombineArgs {
     const float *out;      // [A,H]

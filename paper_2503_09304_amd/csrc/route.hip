@@ -156,15 +156,24 @@ __global__ __launch_bounds__(256) void topk_softmax(const float *__restrict__ lo
 
 }  // namespace
 
+hipError_t launch_pack_gate(const void *Wg, void *WgT, int H, int E, hipStream_t s) {
+    const int E16 = (E + 15) / 16 * 16;
+    const long tot = (long)E16 * H;
+    hipLaunchKernelGGL(wg_transpose_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s, (const uint16_t *)Wg,
+                       (uint16_t *)WgT, H, E, E16);
+    return hipGetLastError();
+}
+
 hipError_t launch_route(const RouteArgs &a, hipStream_t s) {
     if (a.N <= 0) return hipSuccess;
     if (a.dtype == MOE_BF16) {
         const int E16 = (a.E + 15) / 16 * 16, nb = E16 / 16;
         const long tot = (long)E16 * a.H;
-        hipLaunchKernelGGL(wg_transpose_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s,
-                           (const uint16_t *)a.Wg, (uint16_t *)a.WgT, a.H, a.E, E16);
+        if (!a.packed)
+            hipLaunchKernelGGL(wg_transpose_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s,
+                               (const uint16_t *)a.Wg, (uint16_t *)a.WgT, a.H, a.E, E16);
         const dim3 g((a.N + 15) / 16), b(256);
-        const uint16_t *x = (const uint16_t *)a.x, *wt = (const uint16_t *)a.WgT;
+        const uint16_t *x = (const uint16_t *)a.x, *wt = (const uint16_t *)(a.packed ? a.Wg : a.WgT);
         if (nb <= 1) hipLaunchKernelGGL(gate_logits_bf16<1>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
         else if (nb <= 2) hipLaunchKernelGGL(gate_logits_bf16<2>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
         else if (nb <= 4) hipLaunchKernelGGL(gate_logits_bf16<4>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);

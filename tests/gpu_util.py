@@ -27,15 +27,34 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 
 class DevWeights:
+    """Weights on the device, row-major; .packed() gives the re-laid-out copy (bf16 only)."""
+
     def __init__(self, w):
         self.Wg, self.W1, self.W3, self.W2 = (to_dev(w[n]) for n in ("Wg", "W1", "W3", "W2"))
         self.struct = q.Context.weights(self.Wg, self.W1, self.W3, self.W2)
+        self._packed = None
+
+    def packed(self) -> "DevWeights":
+        if self._packed is None:
+            H, E = self.Wg.shape
+            F = self.W1.shape[1]
+            p = object.__new__(DevWeights)
+            p.Wg = torch.empty(((E + 15) // 16 * 16, H), dtype=self.Wg.dtype, device=DEV)
+            p.W1, p.W3, p.W2 = (torch.empty_like(t) for t in (self.W1, self.W3, self.W2))
+            p.struct = q.Context.weights(p.Wg, p.W1, p.W3, p.W2)
+            cfg = q.MoeConfig(E, 1, H, F, q.MOE_BF16, 1, 0)
+            q.moe_pack_weights(cfg, self.struct, p.struct)
+            torch.cuda.synchronize()
+            p._packed = p
+            self._packed = p
+        return self._packed
 
 
 class GpuLayer:
     """One layer-batch on the device."""
 
-    def __init__(self, inp: wl.LayerInputs, dev_w: DevWeights | None = None, max_tokens: int | None = None):
+    def __init__(self, inp: wl.LayerInputs, dev_w: DevWeights | None = None, max_tokens: int | None = None,
+                 down_ksplit: int = 0):
         cfg = inp.cfg
         self.cfg = cfg
         self.inp = inp
@@ -44,7 +63,8 @@ class GpuLayer:
         self.prio = torch.from_numpy(inp.prio).to(DEV)
         self.bias = None if inp.bias is None else torch.from_numpy(inp.bias).to(DEV)
         dt = q.MOE_BF16 if cfg.dtype == "bf16" else q.MOE_F32
-        self.ctx = q.Context(cfg.E, cfg.k, cfg.H, cfg.F, dt, cfg.chunk_rows, max_tokens or max(cfg.N, 1))
+        self.ctx = q.Context(cfg.E, cfg.k, cfg.H, cfg.F, dt, cfg.chunk_rows, max_tokens or max(cfg.N, 1),
+                             down_ksplit=down_ksplit)
         self.y = torch.full((cfg.N, cfg.H), float("nan"), dtype=self.x.dtype, device=DEV)
 
     def route_permute(self):

@@ -136,6 +136,52 @@ def test_reduced_size_cases_match_oracle_and_survive_preemption(name, cfg):
     if nu > 1:
         assert_bit_identical(inp, wl.cut_points(cfg.seed, range(1, nu), 4), base=g)
         assert_bit_identical(inp, tuple(range(1, nu)), base=g)          # one unit per call
+    if cfg.dtype == "bf16":
+        # the packed weight layout computes the same bits, preempted or not
+        pk = g.dw.packed()
+        assert pk.struct.layout == q.MOE_W_PACKED
+        gp, _ = check_layer(inp, dev_w=pk)
+        assert torch.equal(bits(gp.y), bits(g.y))
+        assert torch.equal(bits(gp.ctx.get("expert_out")), bits(g.ctx.get("expert_out")))
+        assert torch.equal(bits(gp.ctx.get("logits")), bits(g.ctx.get("logits")))
+        if nu > 1:
+            assert_bit_identical(inp, wl.cut_points(cfg.seed + 1, range(1, nu), 3), dev_w=pk, base=gp)
+
+
+@pytest.mark.parametrize("ks", [1, 4])
+def test_down_projection_k_split_is_a_configuration_choice(ks):
+    """Both settings match the oracle and are bit-stable under preemption; auto picks per config."""
+    cfg = wl.LayerConfig("ks", dtype="bf16", seed=930 + ks, E=8, k=2, H=256, F=512, N=700, n_ls=150, chunk_rows=128)
+    inp = wl.make_inputs(cfg)
+    lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    lay.run()
+    y_ref, _ = lay.y()
+    base = GpuLayer(inp, down_ksplit=ks).full()
+    assert rel_err(wl.as_f64(to_host(base.y)), y_ref) <= TOL["bf16"]
+    nu = len(base.ctx.units())
+    for cuts in (wl.cut_points(ks, range(1, nu), 5), tuple(range(1, nu))):
+        other = GpuLayer(inp, base.dw, down_ksplit=ks).full(cuts)
+        assert torch.equal(bits(base.y), bits(other.y))
+        assert torch.equal(bits(base.ctx.get("expert_out")), bits(other.ctx.get("expert_out")))
+    with pytest.raises(q.MoeError):
+        q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 512, q.MOE_BF16, 64, 16, 3))
+    with pytest.raises(q.MoeError):
+        q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 192, q.MOE_BF16, 64, 16, 4))     # F not a multiple of 256
+    with pytest.raises(q.MoeError):
+        q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 512, q.MOE_F32, 64, 16, 4))
+
+
+def test_pack_weights_argument_checks():
+    cfg = q.MoeConfig(4, 2, 64, 64, q.MOE_F32, 16, 8)
+    w = q.MoeWeights(256, 512, 768, 1024, 0)
+    d = q.MoeWeights(2560, 5120, 7680, 10240, 0)
+    with pytest.raises(q.MoeError):
+        q.moe_pack_weights(cfg, w, d)                       # fp32 is not packable
+    cfg = q.MoeConfig(4, 2, 64, 64, q.MOE_BF16, 16, 8)
+    with pytest.raises(q.MoeError):
+        q.moe_pack_weights(cfg, w, q.MoeWeights(256, 5120, 7680, 10240, 0))   # in place
+    with pytest.raises(q.MoeError):
+        q.moe_pack_weights(cfg, q.MoeWeights(256, 512, 768, 1024, 1), d)      # source already packed
 
 
 def test_empty_batch_and_k1_weights():

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def mixtral():
     w = wl.make_weights(wl.CONFIGS["cfg2"])
-    return w, DevWeights(w)
+    return w, DevWeights(w).packed()       # the layout the benchmark times
 
 
 def sample(cfg, n, seed=0):
@@ -86,7 +86,7 @@ def test_cfg3_ls_batch_preempts_a_be_prompt(mixtral):
 def test_cfg5_fine_grained_skewed_with_four_preemptions():
     cfg = wl.CONFIGS["cfg5"]
     inp = wl.make_inputs(cfg)
-    g, r = check_layer(inp, sample_tokens=sample(cfg, 32))
+    g, r = check_layer(inp, sample_tokens=sample(cfg, 32), dev_w=DevWeights(inp.w).packed())
     tot = r["counts"].sum(1)
     say(f"  rows per expert: max {tot.max()} min {tot.min()}; units {len(g.ctx.units())}")
     units = g.ctx.units()
