@@ -9,7 +9,8 @@ import os
 from typing import Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libqmoe.so")
+# QMOE_LIB overrides the library file (to try an experimental build); the default is the in-tree one.
+_LIB_PATH = os.environ.get("QMOE_LIB") or os.path.join(_HERE, "libqmoe.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_OK, MOE_DONE = 0, 1

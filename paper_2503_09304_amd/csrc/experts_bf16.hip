@@ -47,6 +47,12 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
 
+// LDS layout of the token tile: rows of 128 bytes = 8 slots of 16 bytes; slot s of row r is stored
+// at slot s ^ swz(r).  swz is a permutation of 0..7 over any 8 consecutive rows, and over 16
+// consecutive rows the pairs (row parity, swz) are all distinct: the 8 or 16 lanes of one
+// ds_read_b128 / ds_write_b128 pass hit distinct banks whether a pass spans 128 or 256 bytes.
+__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Register
 // arrays are only ever indexed with these constants, so they stay in registers.
 template <int N, class F, int... I>
@@ -129,7 +135,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 
     // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
     // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
-    constexpr int DA = D >= 3 ? D : 1;   // token pieces: same distance, or 1 where registers are scarce
+    constexpr int DA = T >= 8 ? 1 : D;   // token pieces: same distance, or 1 where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
     bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]
@@ -147,7 +153,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         static_for<T>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             const int r = srow + 32 * j;
-            *reinterpret_cast<u32x4 *>(lds + stage * STAGE + (r * 8 + (sslot ^ (r & 7))) * 16) = a_reg[S * T + j];
+            *reinterpret_cast<u32x4 *>(lds + stage * STAGE + (r * 8 + (sslot ^ swz(r))) * 16) = a_reg[S * T + j];
         });
     };
     auto load_b = [&](int it, auto setc) {
@@ -168,7 +174,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         static_for<HT>([&](auto tc) {
             constexpr int t = h * HT + decltype(tc)::value;
             const int r = t * 32 + lr;
-            const int slot = (ks * 2 + lh) ^ (r & 7);
+            const int slot = (ks * 2 + lh) ^ swz(r);
             af[(hs & 1) * HT + decltype(tc)::value] = *reinterpret_cast<const bf16x8 *>(lds + stage * STAGE + (r * 8 + slot) * 16);
         });
     };
@@ -186,19 +192,37 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
             });
         });
     };
-    // Iteration `it`, position i = it mod U in the unrolled loop: request the operands of it+D, run
-    // the MFMAs of it, then move the token pieces of it+1 (requested earlier) into the
-    // other LDS stage.  Loads complete in issue order, so neither wait disturbs the iterations of
-    // weight loads issued after the data waited for.  The scheduling barriers keep the compiler
-    // from moving loads across the phases, which would change what the waits cover.
+    // The instruction mix of one iteration, handed to the scheduler as one pipeline: the MFMAs are
+    // the backbone (2 per slot); each slot also takes one LDS fragment read; the T+8 global loads
+    // are spread over the first half of the slots (so the texture path works under the MFMAs
+    // instead of in a burst), the T LDS writes of the next token tile over the last slots.
+    auto pipeline = [&]() {
+        constexpr int NS = 4 * T, NV = T + 8, HALF = NS / 2;
+        __builtin_amdgcn_sched_group_barrier(0x100, HT, 0);
+        static_for<NS>([&](auto sc) {
+            constexpr int sl = decltype(sc)::value;
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            if constexpr (sl < NS - HT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if constexpr (sl < HALF) {
+                constexpr int vm = NV / HALF + (sl < NV % HALF ? 1 : 0);
+                if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);
+            }
+            if constexpr (sl >= NS - T) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        });
+    };
+    // Iteration `it`, position i = it mod U in the unrolled loop: request the operands of it+D (token
+    // pieces first: the wait for them must not cover the weight loads), run the MFMAs of it, move the
+    // token pieces of it+1 (requested earlier) into the other LDS stage.  Loads complete in issue
+    // order, so neither wait disturbs the iterations of weight loads issued after the data waited for.
     auto body = [&](int it, auto ic) {
         constexpr int i = decltype(ic)::value;
+        __builtin_amdgcn_sched_barrier(0);
         load_a(it + DA, std::integral_constant<int, (i + DA) % NA>{});
         load_b(it + D, std::integral_constant<int, (i + D) % NB>{});
-        __builtin_amdgcn_sched_barrier(0);
         mfma_tile(it & 1, std::integral_constant<int, i % NB>{});
-        __builtin_amdgcn_sched_barrier(0);
         store_a((it + 1) & 1, std::integral_constant<int, (i + 1) % NA>{});
+        pipeline();
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     };
 
@@ -285,7 +309,7 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
     if (TCAP >= 8 && t_cnt > 4) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else expert_tile<1, GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
 }
 

@@ -18,7 +18,7 @@ constexpr int kMaxChunkRows = 256;
 
 // A launch of at most this many row segments carries them in its kernel arguments (and may merge
 // row-adjacent units of one expert into one segment); larger launches read the device unit list.
-constexpr int kMaxSegs = 256;
+constexpr int kMaxSegs = 384;
 
 // Rows [row0, row0+rows) of the sorted order, all of one expert: what one workgroup column works on.
 struct Seg {
