@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE-layer hot path on one MI355X.
 
-A step is one pass of the whole path over one batch: moe_route -> moe_permute -> moe_expert_run
-(to completion) -> moe_combine, inputs already resident in HBM.  The default workload is the
-Mixtral-shaped bf16 prefill batch (512 tokens, 128 LS + 384 BE, 8 experts top-2, H 4096, F 14336),
-seeded synthetic data.  Prints ONE JSON line with the throughput, the roofline figure of the
-dominant kernel (timed with HIP events on the launch stream, inside the timed region) and the CPU
-oracle timed on a bounded sample of the same workload.
+Throughput (default).  A step is one pass of the whole path over one batch: moe_route ->
+moe_permute -> moe_expert_run (to completion) -> moe_combine, inputs already resident in HBM.  The
+default workload is the Mixtral-shaped bf16 prefill batch (512 tokens, 128 LS + 384 BE, 8 experts
+top-2, H 4096, F 14336), seeded synthetic data.  Prints ONE JSON line with the throughput, the
+roofline figure of the dominant kernel (timed with HIP events on the launch stream, inside the
+timed region), the CPU oracle timed on a bounded sample of the same workload and, for the Mixtral
+weights, the LS completion latency when a 3584-token BE prompt is in flight (--latency-trials).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg5|cfg3_be|cfg3_ls]
 """
@@ -22,8 +23,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+# HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def log(*a):
@@ -32,16 +37,112 @@ def log(*a):
 
 def gate_up_bytes(cfg, counts, es):
     """Algorithmic HBM bytes of the gate-up launch of a run-to-completion call: W1 and W3 of every
-    expert once per priority phase in which it has rows, the gathered x rows once, the activation
-    written once."""
-    touched = int((counts > 0).sum())          # (expert, phase) pairs with work
-    w = touched * 2 * cfg.F * cfg.H * es
-    return w + cfg.A * cfg.H * es + cfg.A * cfg.F * es
+    expert that has rows, once (the launch merges an expert's LS and BE rows into one pass over
+    its weights), the gathered x rows once, the activation written once."""
+    touched = int((counts.sum(1) > 0).sum())
+    return touched * 2 * cfg.F * cfg.H * es + cfg.A * cfg.H * es + cfg.A * cfg.F * es
 
 
-def down_bytes(cfg, counts, es):
-    touched = int((counts > 0).sum())
-    return touched * cfg.H * cfg.F * es + cfg.A * cfg.F * es + cfg.A * cfg.H * 4
+def down_bytes(cfg, counts, es, ksplit):
+    touched = int((counts.sum(1) > 0).sum())
+    planes = 4 * cfg.A * cfg.H * 4 * 2 if ksplit == 4 else 0     # partial planes written, then read
+    return touched * cfg.H * cfg.F * es + cfg.A * cfg.F * es + cfg.A * cfg.H * 4 + planes
+
+
+def pct(v, p):
+    import numpy as np
+    return float(np.percentile(np.asarray(v), p))
+
+
+def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, seed=77):
+    """LS completion latency when a BE prompt is in flight (cfg3): the BE context is fed
+    `units_per_call` work units per moe_expert_run with at most `lookahead` calls outstanding; at a
+    seeded offset into the BE layer an LS batch arrives, the host stops feeding BE, runs the LS
+    context to completion and resumes BE from its cursor.  Latency = arrival -> the host sees the
+    LS combine finished."""
+    import numpy as np
+    cbe, cls_ = wl.CONFIGS["cfg3_be"], wl.CONFIGS["cfg3_ls"]
+    be = GpuLayer(wl.make_inputs(cbe, weights={}), dw)
+    ls = GpuLayer(wl.make_inputs(cls_, weights={}), dw)
+
+    def run_ls():
+        ls.route_permute(); ls.run(); ls.combine(q.MOE_CLASS_LS)
+
+    def run_be_all():
+        be.route_permute(); be.run(); be.combine()
+
+    for _ in range(3):
+        run_be_all(); run_ls()
+    torch.cuda.synchronize()
+    # references: BE alone, LS alone on an idle GPU
+    t = []
+    for _ in range(5):
+        torch.cuda.synchronize(); t0 = time.perf_counter(); run_be_all(); torch.cuda.synchronize()
+        t.append(time.perf_counter() - t0)
+    be_ms = 1e3 * min(t)
+    y_ref = be.y.clone()
+    t = []
+    for _ in range(10):
+        torch.cuda.synchronize(); t0 = time.perf_counter(); run_ls(); torch.cuda.synchronize()
+        t.append(time.perf_counter() - t0)
+    ls_alone_ms = 1e3 * float(np.median(t))
+
+    rng = np.random.default_rng(seed)
+    offsets = rng.uniform(0.02, 0.95, size=trials) * be_ms * 1e-3
+    lat, lat_nopre, waited_units, identical = [], [], [], True
+    for i, off in enumerate(offsets):
+        # --- run-to-completion baseline: the BE layer is enqueued whole; LS waits behind it
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_be_all()
+        while time.perf_counter() - t0 < off:
+            pass
+        run_ls()
+        torch.cuda.synchronize()
+        lat_nopre.append(time.perf_counter() - (t0 + off))
+        # --- preemptive: bounded look-ahead, stop at the next expert-chunk boundary
+        be.y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        cur = be.route_permute()
+        pending, done, arrived, t_done = [], False, False, None
+        while not done or pending:
+            now = time.perf_counter() - t0
+            if not arrived and now >= off:
+                arrived = True
+                waited_units.append(len(pending) * units_per_call)
+                run_ls()
+                ev = torch.cuda.Event(); ev.record()
+                ev.synchronize()
+                t_done = time.perf_counter() - t0
+                continue
+            while pending and pending[0].query():
+                pending.pop(0)
+            if not done and len(pending) < lookahead:
+                rc = be.run(units_per_call)
+                ev = torch.cuda.Event(); ev.record(); pending.append(ev)
+                done = rc == q.MOE_DONE
+        if not arrived:                       # BE finished before the arrival time: LS runs on an idle GPU
+            while time.perf_counter() - t0 < off:
+                pass
+            run_ls(); torch.cuda.synchronize()
+            t_done = time.perf_counter() - t0
+        be.combine()
+        torch.cuda.synchronize()
+        lat.append(t_done - off)
+        if i < 8:
+            identical = identical and bool(torch.equal(be.y.view(torch.int16), y_ref.view(torch.int16)))
+    ms = lambda v: round(1e3 * v, 4)
+    return {
+        "workload": "cfg3: 3584-token BE prompt in flight (28 units of <=256 rows), 512-token LS batch arrives",
+        "trials": trials, "units_per_call": units_per_call, "lookahead_calls": lookahead,
+        "ls_latency_ms": {"p50": ms(pct(lat, 50)), "p99": ms(pct(lat, 99)), "max": ms(max(lat))},
+        "ls_alone_idle_gpu_ms": round(ls_alone_ms, 4),
+        "ls_latency_no_preemption_ms": {"p50": ms(pct(lat_nopre, 50)), "p99": ms(pct(lat_nopre, 99))},
+        "be_layer_uninterrupted_ms": round(be_ms, 4),
+        "be_units_enqueued_at_arrival_mean": round(float(np.mean(waited_units)), 2) if waited_units else 0.0,
+        "be_output_bit_identical_after_resume": identical,
+    }
 
 
 def main() -> int:
@@ -53,6 +154,10 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rowmajor", action="store_true", help="keep the weights row-major (default: packed at load)")
+    ap.add_argument("--latency-trials", type=int, default=40,
+                    help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
+    ap.add_argument("--units-per-call", type=int, default=1)
+    ap.add_argument("--lookahead", type=int, default=2)
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the yardstick for HBM byte counters")
     args = ap.parse_args()
@@ -82,18 +187,18 @@ def main() -> int:
         dw = dw.packed()          # one-time re-layout at model load, outside the timed region
     g = GpuLayer(inp, dw)
     torch.cuda.synchronize()
-
-    def step():
-        g.route_permute()
-        g.run()
-        g.combine()
-
     if args.calib_copy:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    def step():
+        g.route_permute()
+        g.run()
+        g.combine()
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -111,8 +216,7 @@ def main() -> int:
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_s = cfg.N / (ms_per_step * 1e-3)
 
-    # ---- per-stage times (separate, untimed-region loop; for the log only)
-    stages = {}
+    # ---- per-stage times (separate loop, for the log only)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     acc = [0.0] * 4
     for _ in range(5):
@@ -125,27 +229,36 @@ def main() -> int:
             acc[i] += ev[i].elapsed_time(ev[i + 1]) / 5
     stages = dict(zip(("route_ms", "permute_ms", "experts_ms", "combine_ms"), (round(v, 4) for v in acc)))
 
+    ksplit = 4 if (cfg.F % 256 == 0 and cfg.N * cfg.k <= 256 * cfg.E) else 1
     gu_ms, gu_n = prof["gate_up"]
     dn_ms = prof["down"][0] + prof["down_reduce"][0]
     gu_avg_ms = gu_ms / max(gu_n, 1)
     gub = gate_up_bytes(cfg, counts, es)
-    dnb = down_bytes(cfg, counts, es)
+    dnb = down_bytes(cfg, counts, es, ksplit)
     flops = wl.flops(cfg)
     gu_flops = 4.0 * cfg.A * cfg.H * cfg.F
     hbm_bound = (gub / (HBM_PEAK_GBS * 1e9)) >= (gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
     if hbm_bound:
         achieved = gub / (gu_avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None}
+                "frac": round(achieved / HBM_PEAK_GBS, 4)}
     else:
         achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4)}
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.rowmajor else None
     roof.update({"kernel": "expert_bf16 gate-up (W1,W3 GEMM + SwiGLU)", "avg_launch_ms": round(gu_avg_ms, 4),
                  "launches": gu_n, "algorithmic_bytes_per_launch": int(gub),
                  "algorithmic_flops_per_launch": gu_flops,
-                 "down_kernel_ms_per_step": round(dn_ms / max(args.steps, 1), 4),
-                 "down_algorithmic_bytes_per_step": int(dnb)})
+                 "down_kernels_ms_per_step": round(dn_ms / max(args.steps, 1), 4),
+                 "down_algorithmic_bytes_per_step": int(dnb),
+                 "down_achieved_GBps": round(dnb / (dn_ms / max(args.steps, 1) * 1e-3) / 1e9, 1) if dn_ms > 0 else None})
+
+    # ---- LS latency while a long BE batch is in flight (Mixtral weights)
+    lat = None
+    if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16":
+        lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead)
+        log("LS latency under BE load:", json.dumps(lat))
 
     # ---- the oracle, as it stands, on a bounded sample of the same workload
     cpu = None
@@ -177,11 +290,14 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} ({cfg.n_ls} LS) H={cfg.H} F={cfg.F} E={cfg.E} top-{cfg.k} "
                                f"chunk_rows={cfg.chunk_rows} seed={cfg.seed}",
-                   "order": "priority-major (LS units, then BE units)",
-                   "weights": "row-major" if args.rowmajor else "packed at load (moe_pack_weights)", "units": int(g.ctx.cursor.n_units)},
+                   "call": "one run-to-completion moe_expert_run (LS units first in the unit list; an expert's "
+                           "LS and BE rows share one pass over its weights)",
+                   "weights": "row-major" if args.rowmajor else "packed at load (moe_pack_weights)",
+                   "units": int(g.ctx.cursor.n_units)},
         "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
         "stages_ms": stages,
         "roofline": roof,
+        "ls_latency_under_be_load": lat,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
