@@ -167,7 +167,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     };
     // MFMAs of one iteration.  Token fragments are read from LDS one half-step (HT tiles of one
     // k-step) ahead of the MFMAs that use them.
-    constexpr int HT = T >= 8 ? 4 : T, NH = T / HT, STEPS = 4 * NH;
+    constexpr int HT = T >= 8 ? 4 : (T == 6 ? 3 : T), NH = T / HT, STEPS = 4 * NH;
     bf16x8 af[2 * HT];
     auto read_af = [&](int stage, auto hsc) {
         constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;
@@ -297,7 +297,7 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
     return true;
 }
 
-// TCAP: largest number of 32-token tiles a unit of this launch may have (1, 2, 4 or 8).  A
+// TCAP: largest number of 32-token tiles a segment of this launch may have (1, 2, 4, 6 or 8).  A
 // workgroup takes the smallest fully unrolled variant that covers its unit.
 template <int TCAP, bool GATEUP, bool PACKED>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
@@ -307,7 +307,8 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     if (!map_block(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
-    if (TCAP >= 8 && t_cnt > 4) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else expert_tile<1, GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
@@ -369,6 +370,7 @@ void launch_t(int tiles, const BArgs &b, bool packed, hipStream_t s) {
     if (tiles <= 1) launch1<1, GATEUP>(b, packed, s);
     else if (tiles <= 2) launch1<2, GATEUP>(b, packed, s);
     else if (tiles <= 4) launch1<4, GATEUP>(b, packed, s);
+    else if (tiles <= 6) launch1<6, GATEUP>(b, packed, s);
     else launch1<8, GATEUP>(b, packed, s);
 }
 

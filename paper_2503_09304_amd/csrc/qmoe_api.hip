@@ -358,21 +358,6 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
                 }
                 segs.push_back(qmoe::Seg{(uint32_t)u.row0, (uint16_t)u.rows, (uint16_t)u.expert});
             }
-            // An expert whose rows in this launch fit one segment is bound by streaming its weights,
-            // not by MFMA: cut the segment into pieces of at most 64 rows.  Their workgroups run side
-            // by side on one XCD, the weights come from HBM once and from L2 for the rest, and the
-            // small tiles leave room for two workgroups per CU, which hides each other's waits.
-            std::vector<qmoe::Seg> cut;
-            for (size_t i = 0; i < segs.size(); ++i) {
-                const bool alone = (i == 0 || segs[i - 1].expert != segs[i].expert) &&
-                                   (i + 1 == segs.size() || segs[i + 1].expert != segs[i].expert);
-                const int rows = segs[i].rows;
-                const int parts = alone ? (rows + 63) / 64 : 1;
-                const int per = (rows + parts - 1) / parts;
-                for (int r = 0; r < rows; r += per)
-                    cut.push_back(qmoe::Seg{segs[i].row0 + (uint32_t)r, (uint16_t)std::min(per, rows - r), segs[i].expert});
-            }
-            if (cut.size() <= (size_t)qmoe::kMaxSegs) segs.swap(cut);
             if (segs.size() > (size_t)qmoe::kMaxSegs) segs.clear();
         }
         if (!segs.empty()) {
