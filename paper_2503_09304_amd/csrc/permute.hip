@@ -3,7 +3,8 @@
 //
 // Assignment a = n*k + slot has bucket key 2*expert + (LS ? 0 : 1).  Sorting the assignments by
 // (key, a) gives, per expert, its LS tokens in arrival order followed by its BE tokens in arrival
-// order.  Three kernels, integer work only:
+// order.  Small batches run the whole sort in one workgroup (perm_fused); larger ones take three
+// kernels, integer work only:
 //   perm_rank    every wave finds, with one ballot per key bit, the lanes that share its key
 //                (rank inside the wave = popcount of the lower lanes); the 16 waves of a workgroup
 //                are chained through LDS counters -> rank inside the 1024-assignment block, and
@@ -138,6 +139,90 @@ __global__ __launch_bounds__(256) void perm_scatter(const int32_t *__restrict__ 
     inv[a] = pos;
 }
 
+// The whole sort in one workgroup, for batches of at most kPermFusedMax assignments (latency
+// matters more than parallelism there): LDS-atomic histogram, bucket scan and unit list, then the
+// blocks of 1024 assignments ranked one after the other with running per-bucket counters.
+constexpr int kPermFusedMax = 8192;
+
+__global__ __launch_bounds__(kPermBlock) void perm_fused(const int32_t *__restrict__ topk_idx, const uint8_t *__restrict__ prio,
+                                                         int A, int k, int E, int C, int nbits, int32_t *__restrict__ cnt,
+                                                         int32_t *__restrict__ off, int32_t *__restrict__ perm,
+                                                         int32_t *__restrict__ inv, uint8_t *__restrict__ cls,
+                                                         moe_unit *__restrict__ units, int32_t *__restrict__ n_units,
+                                                         int max_units) {
+    extern __shared__ int32_t sm[];
+    const int nb = 2 * E, tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    int32_t *tot = sm, *boff = sm + nb, *ustart = sm + 2 * nb, *tmp = sm + 3 * nb, *running = sm + 4 * nb;
+    int32_t *wavecnt = sm + 5 * nb;  // [16][nb]
+    for (int b = tid; b < nb; b += kPermBlock) { tot[b] = 0; running[b] = 0; }
+    __syncthreads();
+    for (int a = tid; a < A; a += kPermBlock) {
+        const int n = a / k;
+        const int c = prio[n] ? 0 : 1;
+        atomicAdd(&tot[topk_idx[a] * 2 + c], 1);
+        if (a - n * k == 0) cls[n] = (uint8_t)c;
+    }
+    __syncthreads();
+    for (int b = tid; b < nb; b += kPermBlock) boff[b] = tot[b];
+    __syncthreads();
+    const int total = block_excl_scan(boff, tmp, nb);
+    for (int b = tid; b < nb; b += kPermBlock) { cnt[b] = tot[b]; off[b] = boff[b]; }
+    if (tid == 0) off[nb] = total;
+    for (int q = tid; q < nb; q += kPermBlock) {
+        const int cl = q / E, e = q - cl * E;
+        ustart[q] = (tot[2 * e + cl] + C - 1) / C;
+    }
+    __syncthreads();
+    const int nu = block_excl_scan(ustart, tmp, nb);
+    if (tid == 0) *n_units = nu;
+    for (int q = tid; q < nb; q += kPermBlock) {
+        const int cl = q / E, e = q - cl * E;
+        const int len = tot[2 * e + cl], first = boff[2 * e + cl];
+        int u = ustart[q];
+        for (int r = 0; r < len; r += C, ++u) {
+            if (u < max_units) {
+                moe_unit v;
+                v.expert = e; v.cls = cl; v.row0 = first + r; v.rows = len - r < C ? len - r : C;
+                units[u] = v;
+            }
+        }
+    }
+    // stable ranks, block by block
+    for (int base = 0; base < A; base += kPermBlock) {
+        for (int i = tid; i < 16 * nb; i += kPermBlock) wavecnt[i] = 0;
+        __syncthreads();
+        const int a = base + tid;
+        const bool valid = a < A;
+        int key = 0;
+        if (valid) key = topk_idx[a] * 2 + (prio[a / k] ? 0 : 1);
+        unsigned long long m = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (key >> b) & 1;
+            const unsigned long long bal = __ballot(valid && bit);
+            m &= bit ? bal : ~bal;
+        }
+        const int r_in_wave = __popcll(m & ((1ull << l) - 1ull));
+        if (valid && r_in_wave == 0) wavecnt[w * nb + key] = __popcll(m);
+        __syncthreads();
+        for (int b = tid; b < nb; b += kPermBlock) {
+            int run = running[b];
+            for (int ww = 0; ww < 16; ++ww) {
+                const int c = wavecnt[ww * nb + b];
+                wavecnt[ww * nb + b] = run;
+                run += c;
+            }
+            running[b] = run;
+        }
+        __syncthreads();
+        if (valid) {
+            const int pos = boff[key] + wavecnt[w * nb + key] + r_in_wave;
+            perm[pos] = a;
+            inv[a] = pos;
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 hipError_t launch_permute(const PermuteArgs &a, hipStream_t s) {
@@ -147,6 +232,12 @@ hipError_t launch_permute(const PermuteArgs &a, hipStream_t s) {
     int nbits = 0;
     while ((1 << nbits) < nb) ++nbits;
     const int nblocks = (A + kPermBlock - 1) / kPermBlock;
+    if (A <= kPermFusedMax) {
+        hipLaunchKernelGGL(perm_fused, dim3(1), dim3(kPermBlock), (size_t)(5 + 16) * nb * sizeof(int32_t), s, a.topk_idx,
+                           a.prio, A, a.k, a.E, a.C, nbits, a.cnt, a.off, a.perm, a.inv, a.cls, a.units, a.n_units,
+                           a.max_units);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(perm_rank, dim3(nblocks), dim3(kPermBlock), (size_t)16 * nb * sizeof(int32_t), s, a.topk_idx,
                        a.prio, A, a.k, nb, nbits, a.rank, a.blockoff, a.cls);
     hipLaunchKernelGGL(perm_scan, dim3(1), dim3(1024), 0, s, a.blockoff, nblocks, a.E, a.C, a.cnt, a.off, a.units,

@@ -76,9 +76,9 @@ Layout make_layout(const moe_config &c) {
     L.logits = take(N * E * 4);
     L.topk_idx = take(A * 4);
     L.topk_w = take(A * 4);
-    L.cnt = take(2 * E * 4);
+    L.cnt = take((2 * E + 1) * 4);      // counts [E][2], then the unit count: read back in one copy
+    L.n_units = L.cnt + 2 * E * 4;
     L.off = take((2 * E + 1) * 4);
-    L.n_units = take(4);
     L.perm = take(A * 4);
     L.inv = take(A * 4);
     L.rank = take(A * 4);
@@ -273,17 +273,13 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
         a.max_units = (int32_t)ctx->lay.max_units;
         hipError_t e = qmoe::launch_permute(a, s);
         if (e != hipSuccess) return hip_fail(e, "moe_permute: launch");
-        // cnt [2E] and n_units are adjacent regions but separately aligned: two small copies.
-        e = hipMemcpyAsync(ctx->pinned, a.cnt, 2 * (size_t)E * sizeof(int32_t), hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(ctx->pinned + 2 * E, a.n_units, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+        e = hipMemcpyAsync(ctx->pinned, a.cnt, (2 * (size_t)E + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s);
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) return hip_fail(e, "moe_permute: reading the counts back");
         ctx->cnt.assign(ctx->pinned, ctx->pinned + 2 * E);
     } else {
-        hipError_t e = hipMemsetAsync(at<void>(ctx, ctx->lay.cnt), 0, 2 * (size_t)E * 4, s);
+        hipError_t e = hipMemsetAsync(at<void>(ctx, ctx->lay.cnt), 0, (2 * (size_t)E + 1) * 4, s);
         if (e == hipSuccess) e = hipMemsetAsync(at<void>(ctx, ctx->lay.off), 0, (2 * (size_t)E + 1) * 4, s);
-        if (e == hipSuccess) e = hipMemsetAsync(at<void>(ctx, ctx->lay.n_units), 0, 4, s);
         if (e != hipSuccess) return hip_fail(e, "moe_permute: clearing the counts");
         ctx->cnt.assign(2 * (size_t)E, 0);
     }

@@ -5,9 +5,10 @@
 // bf16: logits come from 16x16x32 bf16 MFMA tiles (16 tokens x 16 experts per tile), fp32
 // accumulation.  Wg is [H,E] with E contiguous, the wrong majorness for MFMA operands, so a
 // small kernel first writes it transposed (and padded to a multiple of 16 experts) into scratch.
-// A workgroup owns 16 tokens; its 4 waves split the hidden dimension into 4 contiguous ranges and
-// add their partial tiles through LDS in wave order, so the summation order is fixed.
-// fp32: one wave per token, lanes stride the hidden dimension, butterfly reduction.
+// A workgroup owns 16 tokens; its 8 waves split the hidden dimension into 8 contiguous ranges and
+// add their partial tiles through LDS in wave order, so the summation order is fixed; the same
+// workgroup then selects the experts (fused, no second launch).
+// fp32: one wave per token, lanes stride the hidden dimension, butterfly reduction; separate top-k.
 // top-k: one wave per token; k rounds of a wave-wide arg-max over (logit desc, index asc).
 #include <hip/hip_runtime.h>
 
@@ -27,31 +28,85 @@ __global__ __launch_bounds__(256) void wg_transpose_bf16(const uint16_t *__restr
     WgT[i] = e < E ? Wg[(long)h * E + e] : (uint16_t)0;
 }
 
-// NB = number of 16-expert blocks held in registers (E16 <= 16*NB).
+// Wave-wide top-k of one token's logits: lane l holds the logits of experts l, l+64, l+128, l+192
+// in v[]; k rounds of an arg-max over (logit descending, expert index ascending), butterfly
+// shuffles; lane j ends up with slot j; weights = softmax over the k selected logits.
+constexpr int kSlots = kMaxExperts / 64;
+__device__ __forceinline__ void wave_topk(const float (&v)[kSlots], int l, int E, int k, int32_t *__restrict__ idx_out,
+                                          float *__restrict__ w_out) {
+    unsigned picked = 0;
+    float my_v = 0.f;
+    int my_e = 0;
+    for (int j = 0; j < k; ++j) {
+        float bv = -INFINITY;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < kSlots; ++c) {
+            const int e = l + 64 * c;
+            const bool ok = e < E && !((picked >> c) & 1u);
+            if (ok && (be == 0x7fffffff || v[c] > bv)) { bv = v[c]; be = e; }   // ascending e: '>' keeps the lowest index
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oe = __shfl_xor(be, o, 64);
+            const bool take = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
+            if (take) { bv = ov; be = oe; }
+        }
+        if ((be & 63) == l) picked |= 1u << (be >> 6);
+        if (l == j) { my_v = bv; my_e = be; }
+    }
+    const float top = __shfl(my_v, 0, 64);
+    const float p = l < k ? expf(my_v - top) : 0.f;
+    float s = p;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (l < k) {
+        idx_out[l] = my_e;
+        w_out[l] = p / s;
+    }
+}
+
+// Gate GEMM and top-k of 16 tokens per workgroup.  NB = number of 16-expert blocks held in
+// registers (E16 <= 16*NB).  The 8 waves split the hidden dimension into 8 contiguous ranges (loads
+// issued 8 k-steps at a time), add their partial tiles through LDS in wave order, and then each
+// wave selects the experts of 2 of the 16 tokens.
 template <int NB>
-__global__ __launch_bounds__(256) void gate_logits_bf16(const uint16_t *__restrict__ x, const uint16_t *__restrict__ WgT,
-                                                        const float *__restrict__ bias, float *__restrict__ logits,
-                                                        int N, int H, int E, int nb) {
-    __shared__ float red[3][NB][4][64];
+__global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict__ x, const uint16_t *__restrict__ WgT,
+                                                      const float *__restrict__ bias, float *__restrict__ logits,
+                                                      int32_t *__restrict__ topk_idx, float *__restrict__ topk_w, int N, int H,
+                                                      int E, int nb, int k) {
+    __shared__ float red[7][NB][4][64];
+    __shared__ float lt[16][NB * 16 + 1];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int t16 = l & 15, q = l >> 4;
     int tok = blockIdx.x * 16 + t16;
     if (tok > N - 1) tok = N - 1;
     const int steps = H / 32;
-    const int per = (steps + 3) / 4;
+    const int per = (steps + 7) / 8;
     const int s0 = w * per, s1 = min(steps, s0 + per);
     f32x4 acc[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     const uint16_t *xa = x + (long)tok * H + q * 8;
     const uint16_t *wb = WgT + (long)t16 * H + q * 8;
-    for (int s = s0; s < s1; ++s) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8 *>(xa + s * 32);
+    constexpr int CH = NB <= 4 ? 8 : 2;   // k-steps whose loads are issued together
+    for (int s = s0; s < s1; s += CH) {
+        bf16x8 a[CH], bv[CH][NB];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            if (b < nb) {
-                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(wb + (long)b * 16 * H + s * 32);
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[b], 0, 0, 0);
+        for (int c = 0; c < CH; ++c) {
+            const int sc = min(s + c, s1 - 1);
+            a[c] = *reinterpret_cast<const bf16x8 *>(xa + sc * 32);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                bv[c][b] = *reinterpret_cast<const bf16x8 *>(wb + (long)min(b, nb - 1) * 16 * H + sc * 32);
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            if (s + c < s1) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    if (b < nb) acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c], bv[c][b], acc[b], 0, 0, 0);
             }
         }
     }
@@ -69,14 +124,31 @@ __global__ __launch_bounds__(256) void gate_logits_bf16(const uint16_t *__restri
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float v = acc[b][r];
-                    v += red[0][b][r][l];
-                    v += red[1][b][r][l];
-                    v += red[2][b][r][l];
-                    const int e = b * 16 + t16;          // D: column = expert
-                    const int t = blockIdx.x * 16 + q * 4 + r;  // D: row = token
-                    if (e < E && t < N) logits[(long)t * E + e] = v + (bias ? bias[e] : 0.f);
+#pragma unroll
+                    for (int ww = 0; ww < 7; ++ww) v += red[ww][b][r][l];
+                    const int e = b * 16 + t16;                 // D: column = expert
+                    const int tl = q * 4 + r;                   // D: row = token (within the 16)
+                    const int t = blockIdx.x * 16 + tl;
+                    const float lv = v + ((bias && e < E) ? bias[e] : 0.f);
+                    lt[tl][e] = lv;
+                    if (e < E && t < N) logits[(long)t * E + e] = lv;
                 }
             }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int tl = w * 2 + h;
+        const int t = blockIdx.x * 16 + tl;
+        if (t < N) {
+            float v[kSlots];
+#pragma unroll
+            for (int c = 0; c < kSlots; ++c) {
+                const int e = l + 64 * c;
+                v[c] = e < E ? lt[tl][e] : -INFINITY;
+            }
+            wave_topk(v, l, E, k, topk_idx + (long)t * k, topk_w + (long)t * k);
         }
     }
 }
@@ -108,50 +180,19 @@ __global__ __launch_bounds__(256) void gate_logits_f32(const float *__restrict__
     }
 }
 
-// One wave per token.  Lane l holds the logits of experts l, l+64, l+128, l+192.
+// One wave per token (fp32 path).
 __global__ __launch_bounds__(256) void topk_softmax(const float *__restrict__ logits, int32_t *__restrict__ topk_idx,
                                                     float *__restrict__ topk_w, int N, int E, int k) {
     const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
     const int tok = blockIdx.x * 4 + w;
     if (tok >= N) return;
-    constexpr int SL = kMaxExperts / 64;
-    float v[SL];
+    float v[kSlots];
 #pragma unroll
-    for (int c = 0; c < SL; ++c) {
+    for (int c = 0; c < kSlots; ++c) {
         const int e = l + 64 * c;
         v[c] = e < E ? logits[(long)tok * E + e] : -INFINITY;
     }
-    unsigned picked = 0;
-    float my_v = 0.f;
-    int my_e = 0;
-    for (int j = 0; j < k; ++j) {
-        float bv = -INFINITY;
-        int be = 0x7fffffff;
-#pragma unroll
-        for (int c = 0; c < SL; ++c) {
-            const int e = l + 64 * c;
-            const bool ok = e < E && !((picked >> c) & 1u);
-            if (ok && (be == 0x7fffffff || v[c] > bv)) { bv = v[c]; be = e; }   // ascending e: '>' keeps the lowest index
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(bv, o, 64);
-            const int oe = __shfl_xor(be, o, 64);
-            const bool take = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
-            if (take) { bv = ov; be = oe; }
-        }
-        if ((be & 63) == l) picked |= 1u << (be >> 6);
-        if (l == j) { my_v = bv; my_e = be; }
-    }
-    const float top = __shfl(my_v, 0, 64);
-    float p = l < k ? expf(my_v - top) : 0.f;
-    float s = p;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (l < k) {
-        topk_idx[(long)tok * k + l] = my_e;
-        topk_w[(long)tok * k + l] = p / s;
-    }
+    wave_topk(v, l, E, k, topk_idx + (long)tok * k, topk_w + (long)tok * k);
 }
 
 }  // namespace
@@ -172,19 +213,21 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s) {
         if (!a.packed)
             hipLaunchKernelGGL(wg_transpose_bf16, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, s,
                                (const uint16_t *)a.Wg, (uint16_t *)a.WgT, a.H, a.E, E16);
-        const dim3 g((a.N + 15) / 16), b(256);
+        const dim3 g((a.N + 15) / 16), b(512);
         const uint16_t *x = (const uint16_t *)a.x, *wt = (const uint16_t *)(a.packed ? a.Wg : a.WgT);
-        if (nb <= 1) hipLaunchKernelGGL(gate_logits_bf16<1>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
-        else if (nb <= 2) hipLaunchKernelGGL(gate_logits_bf16<2>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
-        else if (nb <= 4) hipLaunchKernelGGL(gate_logits_bf16<4>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
-        else if (nb <= 8) hipLaunchKernelGGL(gate_logits_bf16<8>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
-        else hipLaunchKernelGGL(gate_logits_bf16<16>, g, b, 0, s, x, wt, a.bias, a.logits, a.N, a.H, a.E, nb);
+#define QMOE_GATE(NBV) hipLaunchKernelGGL(gate_topk_bf16<NBV>, g, b, 0, s, x, wt, a.bias, a.logits, a.topk_idx, a.topk_w, a.N, a.H, a.E, nb, a.k)
+        if (nb <= 1) QMOE_GATE(1);
+        else if (nb <= 2) QMOE_GATE(2);
+        else if (nb <= 4) QMOE_GATE(4);
+        else if (nb <= 8) QMOE_GATE(8);
+        else QMOE_GATE(16);
+#undef QMOE_GATE
     } else {
         hipLaunchKernelGGL(gate_logits_f32, dim3((a.N + 3) / 4), dim3(256), 0, s, (const float *)a.x,
                            (const float *)a.Wg, a.bias, a.logits, a.N, a.H, a.E);
+        hipLaunchKernelGGL(topk_softmax, dim3((a.N + 3) / 4), dim3(256), 0, s, (const float *)a.logits, a.topk_idx,
+                           a.topk_w, a.N, a.E, a.k);
     }
-    hipLaunchKernelGGL(topk_softmax, dim3((a.N + 3) / 4), dim3(256), 0, s, (const float *)a.logits, a.topk_idx,
-                       a.topk_w, a.N, a.E, a.k);
     return hipGetLastError();
 }
 
