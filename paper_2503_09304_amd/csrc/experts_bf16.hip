@@ -246,27 +246,57 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     });
 
     // ---- epilogue.  D register r of lane l: token 8*(r/4) + 4*(l/32) + r%4, weight row l%32 ----
-    static_for<T>([&](auto tc) {
-        constexpr int t = decltype(tc)::value;
+    if (GATEUP) {
+        // SwiGLU in fp32, one rounding to bf16; the wave's [T*32 tokens][32 f] tile goes through LDS
+        // (free after the last barrier of the main loop) so that it leaves as 16-byte stores.
+        __bf16 *st = reinterpret_cast<__bf16 *>(lds) + w * (ROWS * 32);
+        static_for<T>([&](auto tc) {
+            constexpr int t = decltype(tc)::value;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = t * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-            if (i < rows) {
-                if (GATEUP) {
-                    const int f = col_base + lr;
-                    if (f < p.ncols) {
-                        const float m = silu_f(acc[t][0][r]) * acc[t][1][r];
-                        ((__bf16 *)p.dst)[(long)(un.row0 + i) * p.ldd + f] = (__bf16)m;
-                    }
-                } else {
-                    const int h0 = col_base + lr, h1 = h0 + 32;
-                    float *o = (float *)p.dst + kq * plane + (long)(un.row0 + i) * p.ldd;
-                    if (h0 < p.ncols) o[h0] = acc[t][0][r];
-                    if (h1 < p.ncols) o[h1] = acc[t][1][r];
-                }
+            for (int r = 0; r < 16; ++r) {
+                const int i = t * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                st[i * 32 + lr] = (__bf16)(silu_f(acc[t][0][r]) * acc[t][1][r]);
+            }
+        });
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // this wave's LDS writes have landed (lgkmcnt 0)
+        __builtin_amdgcn_wave_barrier();
+        const int f0 = col_base + (l & 3) * 8;
+#pragma unroll
+        for (int j = 0; j < 2 * T; ++j) {
+            const int i = (l >> 2) + 16 * j;
+            if (i < rows && f0 < p.ncols) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(st + i * 32 + (l & 3) * 8);
+                *reinterpret_cast<u32x4 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + f0) = v;
             }
         }
-    });
+    } else {
+        // fp32 tile of 32 tokens x 64 columns at a time through this wave's 8 KiB of LDS, so that it
+        // leaves as 16-byte stores (256 contiguous bytes per token row).
+        float *st = reinterpret_cast<float *>(lds) + w * (32 * 64);
+        float *obase = (float *)p.dst + kq * plane + (long)un.row0 * p.ldd + col_base + (l & 15) * 4;
+        const bool col_ok = col_base + (l & 15) * 4 < p.ncols;
+        static_for<T>([&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            if (t * 32 < rows) {
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = 8 * (r >> 2) + 4 * lh + (r & 3);
+                    st[i * 64 + lr] = acc[t][0][r];
+                    st[i * 64 + 32 + lr] = acc[t][1][r];
+                }
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int i = (l >> 4) + 4 * j;
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(st + i * 64 + (l & 15) * 4);
+                    if (t * 32 + i < rows && col_ok) *reinterpret_cast<f32x4 *>(obase + (long)(t * 32 + i) * p.ldd) = v;
+                }
+                __builtin_amdgcn_s_waitcnt(0xc07f);
+            }
+        });
+    }
 }
 
 // Workgroup id -> (unit, column tile, K quarter).  The hardware deals consecutive workgroup ids
@@ -301,7 +331,8 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
 // workgroup takes the smallest fully unrolled variant that covers its unit.
 template <int TCAP, bool GATEUP, bool PACKED>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
-    __shared__ __attribute__((aligned(16))) char lds[2 * TCAP * 32 * 128];
+    // two token-tile stages; at least 8 KiB per wave for the epilogue's store staging
+    __shared__ __attribute__((aligned(16))) char lds[(2 * TCAP * 32 * 128) > 32768 ? (2 * TCAP * 32 * 128) : 32768];
     int ct, kq;
     moe_unit un;
     if (!map_block(b, un, ct, kq)) return;
