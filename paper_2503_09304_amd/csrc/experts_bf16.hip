@@ -167,7 +167,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     };
     // MFMAs of one iteration.  Token fragments are read from LDS one half-step (HT tiles of one
     // k-step) ahead of the MFMAs that use them.
-    constexpr int HT = T >= 8 ? 4 : (T == 6 ? 3 : T), NH = T / HT, STEPS = 4 * NH;
+        constexpr int HT = T >= 8 ? 4 : (T == 6 ? 3 : T), NH = T / HT, STEPS = 4 * NH;
     bf16x8 af[2 * HT];
     auto read_af = [&](int stage, auto hsc) {
         constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;

@@ -171,6 +171,33 @@ def test_down_projection_k_split_is_a_configuration_choice(ks):
         q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 512, q.MOE_F32, 64, 16, 4))
 
 
+def test_packed_layout_is_the_documented_permutation():
+    """moe_pack_weights against the index formula of qmoe.h, written out in numpy: byte-exact."""
+    E, F, H = 3, 128, 192
+    rng = np.random.default_rng(5)
+    w = {"Wg": rng.integers(0, 65536, size=(H, E), dtype=np.uint16),
+         "W1": rng.integers(0, 65536, size=(E, F, H), dtype=np.uint16),
+         "W3": rng.integers(0, 65536, size=(E, F, H), dtype=np.uint16),
+         "W2": rng.integers(0, 65536, size=(E, H, F), dtype=np.uint16)}
+    pk = DevWeights(w).packed()
+
+    def ref(m):                                   # m [E,R,K] -> packed order
+        e_, R, K = m.shape
+        out = np.empty(e_ * R * K, dtype=np.uint16)
+        r, k = np.meshgrid(np.arange(R), np.arange(K), indexing="ij")
+        dst = (((r // 32) * (K // 16) + k // 16) * 64 + (r % 32) + 32 * ((k % 16) // 8)) * 8 + k % 8
+        for e in range(e_):
+            out[e * R * K + dst.reshape(-1)] = m[e].reshape(-1)
+        return out
+
+    for name in ("W1", "W3", "W2"):
+        got = to_host(getattr(pk, name)).reshape(-1)
+        assert np.array_equal(got, ref(w[name])), name
+    wgt = to_host(pk.Wg)
+    assert wgt.shape == (16, H)
+    assert np.array_equal(wgt[:E], w["Wg"].T) and not wgt[E:].any()
+
+
 def test_pack_weights_argument_checks():
     cfg = q.MoeConfig(4, 2, 64, 64, q.MOE_F32, 16, 8)
     w = q.MoeWeights(256, 512, 768, 1024, 0)
