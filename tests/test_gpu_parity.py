@@ -71,7 +71,12 @@ def check_layer(inp, cuts=(), sample_tokens=None, dev_w=None):
         y_got = wl.as_f64(r["y"])[toks]
         e_o = float("nan")
     e_y = rel_err(y_got, y_ref)
-    say(f"  rel err: logits {e_logit:.2e}  expert_out {e_o:.2e}  y {e_y:.2e}  (tol {TOL[cfg.dtype]})")
+    floor = ""
+    if cfg.dtype == "bf16":
+        # what rounding the exact result to the bf16 output type would cost by itself
+        y_rounded = wl.as_f64(wl.f32_to_bf16_bits(np.asarray(y_ref, dtype=np.float32)))
+        floor = f"  [bf16 output rounding alone: {rel_err(y_rounded, y_ref):.2e}]"
+    say(f"  rel err: logits {e_logit:.2e}  expert_out {e_o:.2e}  y {e_y:.2e}  (tol {TOL[cfg.dtype]}){floor}")
     assert np.isfinite(y_got).all()
     assert e_y <= TOL[cfg.dtype]
     if sample_tokens is None:
