@@ -131,6 +131,9 @@ def small_cases():
     yield "bf16_one_token", wl.LayerConfig("s11", **{**base, "N": 1, "n_ls": 1, "seed": 920})
     yield "bf16_many_experts", wl.LayerConfig("s12", dtype="bf16", seed=921, E=256, k=6, H=128, F=128, N=257,
                                               n_ls=64, chunk_rows=32)
+    # more row segments than fit the kernel arguments: the launch reads the device unit list instead
+    yield "bf16_many_segments", wl.LayerConfig("s13", dtype="bf16", seed=922, E=64, k=8, H=128, F=128, N=16384,
+                                               n_ls=4000, chunk_rows=256)
 
 
 @pytest.mark.parametrize("name,cfg", list(small_cases()), ids=[n for n, _ in small_cases()])
