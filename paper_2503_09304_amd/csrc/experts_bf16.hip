@@ -74,7 +74,7 @@ struct BArgs {
 };
 
 // One (unit, column tile, K range) on a workgroup.
-template <int T, bool GATEUP, bool PACKED, int D>
+template <int T, bool GATEUP, bool PACKED, bool STREAM, int D>
 __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, const int ct, const int kq, const int ksplit,
                                             const long plane, char *lds) {
     constexpr int ROWS = T * 32;
@@ -161,8 +161,15 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         const int itc = min(it, iters - 1);
         static_for<4>([&](auto kc) {
             constexpr int ks = decltype(kc)::value;
-            b_reg[S * 8 + ks * 2 + 0] = *reinterpret_cast<const bf16x8 *>(bptr[0] + (long)itc * BIT + ks * BKS);
-            b_reg[S * 8 + ks * 2 + 1] = *reinterpret_cast<const bf16x8 *>(bptr[1] + (long)itc * BIT + ks * BKS);
+            const bf16x8 *q0 = reinterpret_cast<const bf16x8 *>(bptr[0] + (long)itc * BIT + ks * BKS);
+            const bf16x8 *q1 = reinterpret_cast<const bf16x8 *>(bptr[1] + (long)itc * BIT + ks * BKS);
+            if constexpr (STREAM) {
+                b_reg[S * 8 + ks * 2 + 0] = __builtin_nontemporal_load(q0);
+                b_reg[S * 8 + ks * 2 + 1] = __builtin_nontemporal_load(q1);
+            } else {
+                b_reg[S * 8 + ks * 2 + 0] = *q0;
+                b_reg[S * 8 + ks * 2 + 1] = *q1;
+            }
         });
     };
     // MFMAs of one iteration.  Token fragments are read from LDS one half-step (HT tiles of one
@@ -329,7 +336,10 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
 
 // TCAP: largest number of 32-token tiles a segment of this launch may have (1, 2, 4, 6 or 8).  A
 // workgroup takes the smallest fully unrolled variant that covers its unit.
-template <int TCAP, bool GATEUP, bool PACKED>
+// STREAM: no two segments of the launch belong to one expert, so every weight element is read by
+// exactly one workgroup: the loads carry the non-temporal hint and do not displace the token tiles
+// in L2.  Where segments share an expert's weights the hint is left off so that L2 serves the re-reads.
+template <int TCAP, bool GATEUP, bool PACKED, bool STREAM>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     // two token-tile stages; at least 8 KiB per wave for the epilogue's store staging
     __shared__ __attribute__((aligned(16))) char lds[(2 * TCAP * 32 * 128) > 32768 ? (2 * TCAP * 32 * 128) : 32768];
@@ -338,11 +348,11 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     if (!map_block(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
-    if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else expert_tile<1, GATEUP, PACKED, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, PACKED, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, PACKED, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, PACKED, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, PACKED, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else expert_tile<1, GATEUP, PACKED, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
 }
 
 // out[r,:] = ((p0 + p1) + p2) + p3 for the rows of the launch.
@@ -386,23 +396,29 @@ __global__ __launch_bounds__(256) void pack_weights_bf16(const uint4 *__restrict
     dst[i] = src[(e * R + r) * (K / 8) + k / 8];
 }
 
-template <int TCAP, bool GATEUP>
+template <int TCAP, bool GATEUP, bool STREAM>
 void launch1(const BArgs &b, bool packed, hipStream_t s) {
     const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : (unsigned)b.k.nu;
     const unsigned ugroups = (n + 3) / 4, ctb = (b.k.col_tiles * b.ksplit + 7) / 8;
     const unsigned packets = ugroups * ctb;
     const unsigned grid = (packets + 7) / 8 * 8 * 32;
-    if (packed) hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, true>), dim3(grid), dim3(256), 0, s, b);
-    else hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, false>), dim3(grid), dim3(256), 0, s, b);
+    if (packed) hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, true, STREAM>), dim3(grid), dim3(256), 0, s, b);
+    else hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, false, STREAM>), dim3(grid), dim3(256), 0, s, b);
+}
+
+template <bool GATEUP, bool STREAM>
+void launch_ts(int tiles, const BArgs &b, bool packed, hipStream_t s) {
+    if (tiles <= 1) launch1<1, GATEUP, STREAM>(b, packed, s);
+    else if (tiles <= 2) launch1<2, GATEUP, STREAM>(b, packed, s);
+    else if (tiles <= 4) launch1<4, GATEUP, STREAM>(b, packed, s);
+    else if (tiles <= 6) launch1<6, GATEUP, STREAM>(b, packed, s);
+    else launch1<8, GATEUP, STREAM>(b, packed, s);
 }
 
 template <bool GATEUP>
-void launch_t(int tiles, const BArgs &b, bool packed, hipStream_t s) {
-    if (tiles <= 1) launch1<1, GATEUP>(b, packed, s);
-    else if (tiles <= 2) launch1<2, GATEUP>(b, packed, s);
-    else if (tiles <= 4) launch1<4, GATEUP>(b, packed, s);
-    else if (tiles <= 6) launch1<6, GATEUP>(b, packed, s);
-    else launch1<8, GATEUP>(b, packed, s);
+void launch_t(int tiles, bool stream, const BArgs &b, bool packed, hipStream_t s) {
+    if (stream) launch_ts<GATEUP, true>(tiles, b, packed, s);
+    else launch_ts<GATEUP, false>(tiles, b, packed, s);
 }
 
 }  // namespace
@@ -422,10 +438,13 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     if (b.nseg > 0) std::copy(a.segs, a.segs + a.nseg, b.seg);
     const int tiles = (a.max_rows + 31) / 32;
     const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : a.nu;
+    // segments are sorted by expert: the weights are streamed once iff no two neighbours share one
+    bool stream = b.nseg > 0;
+    for (int i = 1; i < b.nseg; ++i) stream = stream && b.seg[i].expert != b.seg[i - 1].expert;
 
     b.k = gu_in;
     b.k.col_tiles = (a.F + 127) / 128;
-    { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch_t<true>(tiles, b, a.packed, s); }
+    { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch_t<true>(tiles, stream, b, a.packed, s); }
 
     b.k = dn_in;
     b.k.col_tiles = (a.H + 255) / 256;
@@ -433,13 +452,13 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
         b.ksplit = 4;
         b.plane = a.plane;
         b.k.dst = a.partial;
-        { Scope sc(a.prof, MOE_PROF_DOWN, s); launch_t<false>(tiles, b, a.packed, s); }
+        { Scope sc(a.prof, MOE_PROF_DOWN, s); launch_t<false>(tiles, stream, b, a.packed, s); }
         const int per_seg = std::max(1, std::min(64, (a.max_rows * (a.H / 4) + 255) / 256));
         Scope sc(a.prof, MOE_PROF_DOWN_REDUCE, s);
         hipLaunchKernelGGL(reduce_planes, dim3(per_seg, n), dim3(256), 0, s, b, (const float *)a.partial, a.out, a.H);
     } else {
         Scope sc(a.prof, MOE_PROF_DOWN, s);
-        launch_t<false>(tiles, b, a.packed, s);
+        launch_t<false>(tiles, stream, b, a.packed, s);
     }
 }
 
