@@ -48,6 +48,15 @@ class MoeError(RuntimeError):
         self.code = code
 
 
+class SchedBatch(C.Structure):
+    _fields_ = [("n", C.c_uint32), ("n_ls", C.c_uint32), ("stage", C.c_int32)]
+
+
+SCHED_OK, SCHED_NONE, SCHED_E_ARG, SCHED_E_JOB = 0, 1, -1, -2
+SCHED_BE, SCHED_LS = 0, 1
+SCHED_PREFILL, SCHED_DECODE = 0, 1
+SCHED_Q_LS_PREFILL, SCHED_Q_BE_PREFILL, SCHED_Q_LS_DECODE, SCHED_Q_BE_DECODE = 0, 1, 2, 3
+
 _lib = None
 
 
@@ -81,6 +90,22 @@ def lib():
         L.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
         for f in ("moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
                   "moe_get", "moe_units", "moe_plan_units"):
+            getattr(L, f).restype = C.c_int32
+        # include/qsched.h
+        L.sched_create.restype = C.c_void_p
+        L.sched_create.argtypes = [C.c_uint32]
+        L.sched_destroy.restype = None
+        L.sched_destroy.argtypes = [C.c_void_p]
+        L.sched_submit.argtypes = [C.c_void_p, C.c_uint64, C.c_int32]
+        L.sched_token.argtypes = [C.c_void_p, C.c_uint64, C.c_int32]
+        L.sched_next_batch.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(SchedBatch)]
+        L.sched_preempt_wanted.argtypes = [C.c_void_p, C.POINTER(SchedBatch)]
+        L.sched_queue_len.restype = C.c_uint32
+        L.sched_queue_len.argtypes = [C.c_void_p, C.c_int32]
+        L.sched_running.restype = C.c_uint32
+        L.sched_running.argtypes = [C.c_void_p]
+        L.sched_last_error.restype = C.c_char_p
+        for f in ("sched_submit", "sched_token", "sched_next_batch", "sched_preempt_wanted"):
             getattr(L, f).restype = C.c_int32
         _lib = L
     return _lib
@@ -221,3 +246,61 @@ class Context:
         if what == "units":
             return raw.view(torch.int32).view(-1, 4)
         raise KeyError(what)
+
+
+class SchedError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"qsched error {code}: {msg}")
+        self.code = code
+
+
+class Scheduler:
+    """The opaque sched object of include/qsched.h; methods are the C calls."""
+
+    def __init__(self, batch_size: int):
+        self.batch_size = batch_size
+        self.h = lib().sched_create(batch_size)
+        if not self.h:
+            raise SchedError(SCHED_E_ARG, lib().sched_last_error().decode())
+        self._ids = (C.c_uint64 * batch_size)()
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().sched_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _check(rc: int) -> int:
+        if rc < 0:
+            raise SchedError(rc, lib().sched_last_error().decode())
+        return rc
+
+    def submit(self, job: int, cls: int) -> None:
+        self._check(lib().sched_submit(self.h, job, cls))
+
+    def token(self, job: int, finished: bool) -> None:
+        self._check(lib().sched_token(self.h, job, 1 if finished else 0))
+
+    def next_batch(self):
+        """(job ids, stage, number of LS jobs), or None when every queue is empty."""
+        b = SchedBatch()
+        rc = self._check(lib().sched_next_batch(self.h, self._ids, self.batch_size, C.byref(b)))
+        if rc == SCHED_NONE:
+            return None
+        return [int(self._ids[i]) for i in range(b.n)], int(b.stage), int(b.n_ls)
+
+    def preempt_wanted(self, running_n_ls: int) -> bool:
+        b = SchedBatch(0, running_n_ls, 0)
+        return self._check(lib().sched_preempt_wanted(self.h, C.byref(b))) == 1
+
+    def queue_len(self, q: int) -> int:
+        return int(lib().sched_queue_len(self.h, q))
+
+    def running(self) -> int:
+        return int(lib().sched_running(self.h))

@@ -14,17 +14,21 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "qmoe.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header, prefix in (("qmoe.h", "moe_"), ("qsched.h", "sched_")):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(%s[a-z_]+)\s*\(" % prefix, text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
     assert {"moe_route", "moe_permute", "moe_expert_run", "moe_combine"} <= set(names)
+    assert {"sched_submit", "sched_token", "sched_next_batch", "sched_preempt_wanted"} <= set(names)
     L = q.lib()
     for n in names:
-        assert hasattr(L, n), f"{n} declared in qmoe.h but not exported"
+        assert hasattr(L, n), f"{n} declared in include/ but not exported"
 
 
 def test_workspace_size_and_config_validation():
