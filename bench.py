@@ -145,8 +145,68 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, se
     }
 
 
+def serve_bench(args) -> int:
+    """Serving comparison above the layer path: a stack of Mixtral-shaped MoE layers, a seeded
+    synthetic request stream (Poisson arrivals, 20 % LS, log-normal lengths), batches of at most 32
+    jobs formed by the C++ scheduler; the preemptive priority-aware policy against the
+    priority-oblivious run-to-completion baseline, at several arrival rates."""
+    import torch
+
+    import paper_2503_09304_amd as q
+    import workloads as wl
+    from paper_2503_09304_amd import serve
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    q.lib()
+    c = wl.CONFIGS["cfg2"]
+    w, keep = serve.synthetic_weights(c.E, c.H, c.F, seed=c.weight_seed or c.seed)
+    rates = [float(r) for r in args.serve_rates.split(",")]
+    rows = []
+    for rate in rates:
+        d = wl.make_jobs(args.serve_jobs, rate, 0.2, seed=9000 + int(rate), max_prompt=args.serve_max_prompt,
+                         max_out=args.serve_max_out)
+        row = {"rate_jobs_per_s": rate}
+        for pre in (False, True):
+            jobs = [serve.Job(i, float(d["arrival_s"][i]), q.SCHED_LS if d["is_ls"][i] else q.SCHED_BE,
+                              int(d["prompt_len"][i]), int(d["out_len"][i])) for i in range(args.serve_jobs)]
+            eng = serve.Engine(w, c.E, c.k, c.H, c.F, layers=args.serve_layers, batch_size=32,
+                               max_prompt=args.serve_max_prompt, preemptive=pre, units_per_call=args.units_per_call,
+                               lookahead=args.lookahead, chunk_rows=c.chunk_rows)
+            warm = [serve.Job(i, 0.0, q.SCHED_BE, args.serve_max_prompt, 2) for i in range(4)]
+            eng.run(warm)                      # first-use costs stay out of the measurement
+            eng.trace.clear()
+            st = eng.run(jobs)
+            log(json.dumps(st))
+            row[st["policy"]] = st
+            del eng
+        a, b = row["fcfs_run_to_completion"], row["preemptive"]
+        row["ls_ttft_mean_speedup"] = round(a["ls"]["ttft_ms"]["mean"] / b["ls"]["ttft_ms"]["mean"], 2)
+        row["ls_turnaround_mean_speedup"] = round(a["ls"]["turnaround_ms"]["mean"] / b["ls"]["turnaround_ms"]["mean"], 2)
+        row["be_turnaround_mean_ratio"] = round(b["be"]["turnaround_ms"]["mean"] / a["be"]["turnaround_ms"]["mean"], 2)
+        row["jobs_per_s_ratio"] = round(b["jobs_per_s"] / a["jobs_per_s"], 3)
+        rows.append(row)
+    out = {"metric": "LS time-to-first-token, preemptive vs run-to-completion, layer-stack level",
+           "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+           "config": {"workload": f"{args.serve_layers} MoE layers of the Mixtral shape (H={c.H} F={c.F} E={c.E} top-{c.k}), "
+                                  f"{args.serve_jobs} jobs per rate, 20% LS, prompts 16..{args.serve_max_prompt} tokens, "
+                                  f"outputs 4..{args.serve_max_out} tokens, batch size 32",
+                      "units_per_call": args.units_per_call, "lookahead_calls": args.lookahead},
+           "rates": rows}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--serve", action="store_true",
+                    help="run the serving comparison (scheduler + layer stack) instead of the layer benchmark")
+    ap.add_argument("--serve-rates", default="40,80,120")
+    ap.add_argument("--serve-jobs", type=int, default=200)
+    ap.add_argument("--serve-layers", type=int, default=8)
+    ap.add_argument("--serve-max-prompt", type=int, default=512)
+    ap.add_argument("--serve-max-out", type=int, default=32)
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
@@ -164,6 +224,8 @@ def main() -> int:
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus must be 1")
         return 2
+    if args.serve:
+        return serve_bench(args)
 
     import numpy as np
     import torch

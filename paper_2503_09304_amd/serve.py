@@ -1,0 +1,224 @@
+"""A serving loop above the layer API: jobs arrive over time, the C++ scheduler (include/qsched.h)
+forms batches with the paper's batch-selection algorithm, and every iteration of a batch runs a stack
+of MoE layers through the C ABI of include/qmoe.h.
+
+Paper: section "System Architecture" (scheduler, dispatcher, batch engine, closed loop between engine
+and scheduler) and the evaluation's workload and metrics (Poisson arrivals, a fraction of the
+prompts marked LS, time to first token, turnaround time, job completion rate).
+
+What is modelled.  A model is `layers` MoE layers; the hidden state entering layer l+1 is x + y of
+layer l (a residual stand-in for the attention block, done with a torch add: the blocks between MoE
+layers are not part of this library).  A prefill iteration runs all prompt tokens of the batch's
+jobs through the stack and yields each job's first token; a decode iteration runs one token per
+job.  Hidden states are rows of a fixed seeded bank, selected by (job, token index).
+
+Two policies share all of that code:
+  * preemptive=True: jobs keep their class; while a batch of BE jobs only is executing, the loop asks
+    the scheduler at every expert-chunk boundary (bounded look-ahead of moe_expert_run calls) whether
+    an LS prompt waits; if so it parks the batch where it is (its context and cursor stay on the
+    device), runs the batch the scheduler hands out next (the LS prefill) through all layers,
+    reports its tokens, and resumes the parked batch from its cursor.
+  * preemptive=False: the priority-oblivious run-to-completion baseline.  Every job is submitted as
+    BE, so the algorithm degenerates to "decode before prefill": a batch, once prefilled, decodes
+    until all its jobs are done before the next prompts are taken; control returns to the scheduler
+    only between iterations.
+Per-row results never depend on the policy (same contexts' configurations, deterministic kernels),
+which `digest=True` lets a test check bit for bit.
+"""
+from __future__ import annotations
+
+import time
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+from . import binding as q
+
+
+@dataclass
+class Job:
+    id: int
+    arrival_s: float
+    cls: int            # q.SCHED_LS or q.SCHED_BE
+    prompt_len: int
+    out_len: int        # output tokens to produce (the first one comes from the prefill)
+    tokens: int = 0
+    ttft_s: float = -1.0
+    done_s: float = -1.0
+
+
+def synthetic_weights(E: int, H: int, F: int, seed: int, device="cuda:0"):
+    """Seeded N(0, 0.02^2) bf16 weights generated on the device, re-laid-out for the expert kernels."""
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+
+    def rnd(*shape):
+        return (torch.randn(*shape, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    Wg = rnd(H, E)
+    W1, W3, W2 = rnd(E, F, H), rnd(E, F, H), rnd(E, H, F)
+    src = q.Context.weights(Wg, W1, W3, W2)
+    pWg = torch.empty(((E + 15) // 16 * 16, H), dtype=torch.bfloat16, device=device)
+    pW1, pW3, pW2 = torch.empty_like(W1), torch.empty_like(W3), torch.empty_like(W2)
+    dst = q.Context.weights(pWg, pW1, pW3, pW2)
+    q.moe_pack_weights(q.MoeConfig(E, 1, H, F, q.MOE_BF16, 1, 0), src, dst)
+    torch.cuda.synchronize()
+    return dst, (pWg, pW1, pW3, pW2)     # the struct and the tensors that keep its memory alive
+
+
+class _Slot:
+    """Buffers and context of one in-flight batch of one stage."""
+
+    def __init__(self, E, k, H, F, chunk_rows, max_tokens, device):
+        self.ctx = q.Context(E, k, H, F, q.MOE_BF16, chunk_rows, max_tokens, device=device)
+        self.x = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
+        self.y = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
+        self.prio = torch.empty(max_tokens, dtype=torch.int32, device=device)
+        self.rows = torch.empty(max_tokens, dtype=torch.int64, device=device)
+        self.owner = torch.empty(max_tokens, dtype=torch.int64, device=device)
+
+
+class Engine:
+    def __init__(self, weights: q.MoeWeights, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
+                 max_prompt: int, preemptive: bool, units_per_call: int = 2, lookahead: int = 2, chunk_rows: int = 256,
+                 bank_rows: int = 4096, seed: int = 1, digest: bool = False, device="cuda:0"):
+        self.w, self.layers, self.batch_size, self.max_prompt = weights, layers, batch_size, max_prompt
+        self.preemptive, self.units_per_call, self.lookahead = preemptive, units_per_call, lookahead
+        self.device = device
+        g = torch.Generator(device=device)
+        g.manual_seed(seed)
+        self.bank = torch.randn(bank_rows, H, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+        self.bank_rows = bank_rows
+        # [stage][level]: level 1 holds the batch that runs while a level-0 batch is parked
+        self.slots = {
+            q.SCHED_PREFILL: [_Slot(E, k, H, F, chunk_rows, batch_size * max_prompt, device) for _ in range(2)],
+            q.SCHED_DECODE: [_Slot(E, k, H, F, chunk_rows, batch_size, device) for _ in range(2)],
+        }
+        self.sched = q.Scheduler(batch_size)
+        self.digest_on = digest
+        self.trace: list = []        # scheduler calls in order, for replay against the oracle
+
+    # ---- dispatcher side ----
+    def _now(self) -> float:
+        return time.perf_counter() - self.t0
+
+    def _admit(self) -> None:
+        """Hand the jobs whose arrival time has passed to the dispatcher."""
+        now = self._now()
+        while self.next_arrival < len(self.arrivals) and self.arrivals[self.next_arrival].arrival_s <= now:
+            j = self.arrivals[self.next_arrival]
+            cls = j.cls if self.preemptive else q.SCHED_BE
+            self.sched.submit(j.id, cls)
+            self.trace.append(("submit", j.id, cls))
+            self.next_arrival += 1
+
+    def _next_batch(self):
+        got = self.sched.next_batch()
+        self.trace.append(("next_batch", got))
+        return got
+
+    # ---- engine side ----
+    def _build(self, slot: _Slot, jobs, stage, n_ls) -> int:
+        rows, prio, owner = [], [], []
+        for i, jid in enumerate(jobs):
+            j = self.jobs[jid]
+            if stage == q.SCHED_PREFILL:
+                r = (j.id * 977 + np.arange(j.prompt_len)) % self.bank_rows
+            else:
+                r = np.array([(j.id * 977 + j.prompt_len + j.tokens) % self.bank_rows])
+            rows.append(r)
+            prio.append(np.full(len(r), 1 if i < n_ls else 0, dtype=np.int32))
+            owner.append(np.full(len(r), j.id, dtype=np.int64))
+        rows, prio, owner = np.concatenate(rows), np.concatenate(prio), np.concatenate(owner)
+        n = len(rows)
+        slot.rows[:n].copy_(torch.from_numpy(rows.astype(np.int64)))
+        slot.prio[:n].copy_(torch.from_numpy(prio))
+        slot.owner[:n].copy_(torch.from_numpy(owner))
+        torch.index_select(self.bank, 0, slot.rows[:n], out=slot.x[:n])
+        return n
+
+    def _iteration(self, jobs, stage, n_ls, level: int) -> None:
+        slot = self.slots[stage][level]
+        n = self._build(slot, jobs, stage, n_ls)
+        x, y, ctx = slot.x[:n], slot.y[:n], slot.ctx
+        preemptible = self.preemptive and level == 0 and n_ls == 0
+        for _ in range(self.layers):
+            ctx.route(x, self.w, n_tokens=n)
+            ctx.permute(slot.prio)
+            if not preemptible:
+                ctx.expert_run(x, self.w)
+            else:
+                pending, done = [], False
+                while not done:
+                    self._admit()
+                    while self.sched.preempt_wanted(0):
+                        self.trace.append(("preempt", tuple(jobs)))
+                        self.preemptions += 1
+                        got = self._next_batch()
+                        self._iteration(*got, level=1)
+                        self._admit()
+                    while pending and pending[0].query():
+                        pending.pop(0)
+                    if len(pending) < self.lookahead:
+                        rc = ctx.expert_run(x, self.w, self.units_per_call)
+                        ev = torch.cuda.Event()
+                        ev.record()
+                        pending.append(ev)
+                        done = rc == q.MOE_DONE
+            ctx.combine(y)
+            x.add_(y)
+        if self.digest_on:
+            h = x.view(torch.int16).to(torch.int32).sum(1, dtype=torch.int64)
+            self.digest.index_add_(0, slot.owner[:n], h)
+        torch.cuda.current_stream().synchronize()
+        now = self._now()
+        self.iterations[stage] += 1
+        for jid in jobs:
+            j = self.jobs[jid]
+            j.tokens += 1
+            if j.tokens == 1:
+                j.ttft_s = now - j.arrival_s
+            fin = j.tokens >= j.out_len
+            if fin:
+                j.done_s = now - j.arrival_s
+                self.finished += 1
+            self.sched.token(jid, fin)
+            self.trace.append(("token", jid, fin))
+
+    def run(self, jobs: list[Job]) -> dict:
+        """Serve the jobs (arrival_s relative to the start of the call); returns the statistics."""
+        self.jobs = {j.id: j for j in jobs}
+        self.arrivals = sorted(jobs, key=lambda j: (j.arrival_s, j.id))
+        self.next_arrival, self.finished, self.preemptions = 0, 0, 0
+        self.iterations = {q.SCHED_PREFILL: 0, q.SCHED_DECODE: 0}
+        self.digest = torch.zeros(max(self.jobs) + 1, dtype=torch.int64, device=self.device)
+        assert all(1 <= j.prompt_len <= self.max_prompt and j.out_len >= 1 for j in jobs)
+        torch.cuda.synchronize()
+        self.t0 = time.perf_counter()
+        while self.finished < len(jobs):
+            self._admit()
+            got = self._next_batch()
+            if got is None:
+                self.trace.pop()             # idle polls are not part of the trace
+                continue
+            self._iteration(*got, level=0)
+        makespan = self._now()
+        return self._stats(makespan)
+
+    def _stats(self, makespan: float) -> dict:
+        out = {"policy": "preemptive" if self.preemptive else "fcfs_run_to_completion", "jobs": len(self.jobs),
+               "makespan_s": round(makespan, 4), "jobs_per_s": round(len(self.jobs) / makespan, 2),
+               "output_tokens_per_s": round(sum(j.out_len for j in self.jobs.values()) / makespan, 1),
+               "preemptions": self.preemptions, "prefill_iterations": self.iterations[q.SCHED_PREFILL],
+               "decode_iterations": self.iterations[q.SCHED_DECODE]}
+        for name, cls in (("ls", q.SCHED_LS), ("be", q.SCHED_BE)):
+            js = [j for j in self.jobs.values() if j.cls == cls]
+            if not js:
+                continue
+            ttft = np.array([j.ttft_s for j in js]) * 1e3
+            turn = np.array([j.done_s for j in js]) * 1e3
+            out[name] = {"n": len(js), "ttft_ms": {"mean": round(float(ttft.mean()), 3), "p50": round(float(np.percentile(ttft, 50)), 3),
+                                                    "p99": round(float(np.percentile(ttft, 99)), 3)},
+                         "turnaround_ms": {"mean": round(float(turn.mean()), 3), "p99": round(float(np.percentile(turn, 99)), 3)}}
+        return out

@@ -222,6 +222,21 @@ def elem_bytes(cfg: LayerConfig) -> int:
     return 4 if cfg.dtype == "f32" else 2
 
 
+def make_jobs(n: int, rate_per_s: float, p_ls: float, seed: int, max_prompt: int = 512, max_out: int = 32,
+              min_prompt: int = 16, min_out: int = 4):
+    """A seeded synthetic request stream standing in for the paper's workload generator (prompts of
+    a public conversation dataset, a random 20 % marked LS, Poisson arrivals): exponential
+    inter-arrival times at `rate_per_s`, log-normal prompt and output lengths clipped to the given
+    ranges, each job LS with probability p_ls.  Returns a dict of arrays, one entry per job."""
+    rng = np.random.default_rng([int(seed), 4242])
+    arrival = np.cumsum(rng.exponential(1.0 / rate_per_s, size=n))
+    prompt = np.clip(np.round(rng.lognormal(mean=math.log(0.25 * max_prompt), sigma=0.9, size=n)), min_prompt, max_prompt)
+    out = np.clip(np.round(rng.lognormal(mean=math.log(0.4 * max_out), sigma=0.7, size=n)), min_out, max_out)
+    is_ls = rng.random(n) < p_ls
+    return {"arrival_s": arrival, "prompt_len": prompt.astype(np.int64), "out_len": out.astype(np.int64),
+            "is_ls": is_ls}
+
+
 if __name__ == "__main__":
     for c in CONFIGS.values():
         print(describe(c), f"flops={flops(c):.3e}", f"ridge_rows~{math.ceil(2.5e15 / 8e12)}")
