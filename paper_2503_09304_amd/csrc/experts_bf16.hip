@@ -325,6 +325,7 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
     if (pos >= n || cq >= b.k.col_tiles * b.ksplit) return false;
     if (b.nseg > 0) {
         const Seg g = b.seg[pos];
+        if (g.rows == 0) return false;      // padding between experts
         un.expert = g.expert; un.cls = 0; un.row0 = (int)g.row0; un.rows = g.rows;
     } else {
         un = b.k.units[b.k.u0 + pos];
@@ -435,7 +436,27 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     b.ksplit = 1;
     b.plane = 0;
     b.nseg = a.segs ? a.nseg : 0;
-    if (b.nseg > 0) std::copy(a.segs, a.segs + a.nseg, b.seg);
+    if (b.nseg > 0) {
+        // Packets are groups of 4 consecutive segments.  Where an expert has several segments, its
+        // groups are padded with empty segments so that no packet spans two experts: the workgroups
+        // of a packet then share one set of weight tiles, fetched into that XCD's L2 once.
+        int n = 0;
+        bool shared = false;
+        for (int i = 1; i < a.nseg; ++i) shared = shared || a.segs[i].expert == a.segs[i - 1].expert;
+        if (shared) {
+            for (int i = 0; i < a.nseg && n <= kMaxSegs; ++i) {
+                if (i > 0 && a.segs[i].expert != a.segs[i - 1].expert)
+                    while ((n & 3) && n < kMaxSegs) b.seg[n++] = Seg{0, 0, a.segs[i - 1].expert};
+                if (n < kMaxSegs) b.seg[n] = a.segs[i];
+                ++n;
+            }
+        }
+        if (!shared || n > kMaxSegs) {
+            std::copy(a.segs, a.segs + a.nseg, b.seg);
+            n = a.nseg;
+        }
+        b.nseg = n;
+    }
     const int tiles = (a.max_rows + 31) / 32;
     const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : a.nu;
     // segments are sorted by expert: the weights are streamed once iff no two neighbours share one
