@@ -193,6 +193,8 @@ class Context:
         return rc
 
     def permute(self, prio) -> MoeCursor:
+        if prio is not None and prio.element_size() != 1:
+            raise TypeError("prio must be a uint8 tensor (one byte per token)")
         _check(lib().moe_permute(self.h, _ptr(prio), C.byref(self.cursor), _stream()))
         return self.cursor
 

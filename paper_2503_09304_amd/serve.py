@@ -28,7 +28,7 @@ which `digest=True` lets a test check bit for bit.
 from __future__ import annotations
 
 import time
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 
 import numpy as np
 import torch
@@ -74,7 +74,7 @@ class _Slot:
         self.ctx = q.Context(E, k, H, F, q.MOE_BF16, chunk_rows, max_tokens, device=device)
         self.x = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
         self.y = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
-        self.prio = torch.empty(max_tokens, dtype=torch.int32, device=device)
+        self.prio = torch.empty(max_tokens, dtype=torch.uint8, device=device)
         self.rows = torch.empty(max_tokens, dtype=torch.int64, device=device)
         self.owner = torch.empty(max_tokens, dtype=torch.int64, device=device)
 
@@ -128,7 +128,7 @@ class Engine:
             else:
                 r = np.array([(j.id * 977 + j.prompt_len + j.tokens) % self.bank_rows])
             rows.append(r)
-            prio.append(np.full(len(r), 1 if i < n_ls else 0, dtype=np.int32))
+            prio.append(np.full(len(r), 1 if i < n_ls else 0, dtype=np.uint8))
             owner.append(np.full(len(r), j.id, dtype=np.int64))
         rows, prio, owner = np.concatenate(rows), np.concatenate(prio), np.concatenate(owner)
         n = len(rows)
@@ -146,6 +146,9 @@ class Engine:
         for _ in range(self.layers):
             ctx.route(x, self.w, n_tokens=n)
             ctx.permute(slot.prio)
+            if self.digest_on:      # rows the layer queued as LS, against what the batch holds
+                self.ls_rows_seen += ctx.get("counts")[:, 0].sum()
+                self.ls_rows_expected += ctx.cfg.k * int(slot.prio[:n].sum().item())
             if not preemptible:
                 ctx.expert_run(x, self.w)
             else:
@@ -193,6 +196,8 @@ class Engine:
         self.next_arrival, self.finished, self.preemptions = 0, 0, 0
         self.iterations = {q.SCHED_PREFILL: 0, q.SCHED_DECODE: 0}
         self.digest = torch.zeros(max(self.jobs) + 1, dtype=torch.int64, device=self.device)
+        self.ls_rows_seen = torch.zeros((), dtype=torch.int64, device=self.device)
+        self.ls_rows_expected = 0
         assert all(1 <= j.prompt_len <= self.max_prompt and j.out_len >= 1 for j in jobs)
         torch.cuda.synchronize()
         self.t0 = time.perf_counter()

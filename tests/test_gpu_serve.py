@@ -65,6 +65,8 @@ def test_stream_completes_and_is_bit_identical_across_policies(weights):
         assert all(j.tokens == j.out_len and j.ttft_s >= 0 and j.done_s >= j.ttft_s for j in jobs)
         assert st["prefill_iterations"] + st["decode_iterations"] == replay(eng.trace, BATCH)
         assert eng.sched.running() == 0 and all(eng.sched.queue_len(i) == 0 for i in range(4))
+        assert int(eng.ls_rows_seen.item()) == eng.ls_rows_expected      # the layers saw the batch's priority flags
+        assert (eng.ls_rows_expected > 0) == pre
         results[pre] = (st, eng.digest.cpu().numpy().copy())
     assert results[False][0]["preemptions"] == 0
     assert results[True][0]["preemptions"] > 0
