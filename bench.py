@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2008410339, "cfg4": 1895565594, "cfg3_be": 5211734104, "cfg5": 3288377158}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2025716848, "cfg4": 1911724565, "cfg3_be": 5219285068, "cfg5": 3336967616}
 
 
 def log(*a):
