@@ -463,6 +463,9 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     // segments are sorted by expert: the weights are streamed once iff no two neighbours share one
     bool stream = b.nseg > 0;
     for (int i = 1; i < b.nseg; ++i) stream = stream && b.seg[i].expert != b.seg[i - 1].expert;
+    // With one segment per expert the order of the segments is free: longest first, so that the
+    // workgroups with the most tiles do not form the tail of the launch.
+    if (stream) std::stable_sort(b.seg, b.seg + b.nseg, [](const Seg &x, const Seg &y) { return x.rows > y.rows; });
 
     b.k = gu_in;
     b.k.col_tiles = (a.F + 127) / 128;
