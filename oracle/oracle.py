@@ -211,18 +211,43 @@ class OracleLayer:
     def n_units(self) -> int:
         return len(self.units)
 
-    def run(self, max_units: Optional[int] = None, rows_filter=None) -> bool:
-        """Execute up to max_units units from the cursor.  Returns True when all are done."""
+    def _execute(self, u: int) -> None:
         if self.O is None:
             self.O = np.full((self.N * self.k, self.H), np.nan, dtype=np.float64)
-        stop = self.n_units if max_units is None else min(self.n_units, self.next_unit + max_units)
-        while self.next_unit < stop:
-            e, _cls, r0, rows = (int(v) for v in self.units[self.next_unit])
-            toks = self.perm[r0:r0 + rows] // self.k
-            self.O[r0:r0 + rows] = expert_rows(self.x, self.w["W1"], self.w["W3"], self.w["W2"], e, toks)
-            self.done[r0:r0 + rows] = 1
-            self.executed[self.next_unit] += 1
+        e, _cls, r0, rows = (int(v) for v in self.units[u])
+        toks = self.perm[r0:r0 + rows] // self.k
+        self.O[r0:r0 + rows] = expert_rows(self.x, self.w["W1"], self.w["W3"], self.w["W2"], e, toks)
+        self.done[r0:r0 + rows] = 1
+        self.executed[u] += 1
+
+    def _advance(self) -> None:
+        while self.next_unit < self.n_units and self.executed[self.next_unit]:
             self.next_unit += 1
+
+    def run(self, max_units: Optional[int] = None, rows_filter=None) -> bool:
+        """Execute the next max_units units that have not run yet, in list order, from the cursor
+        (the first unit that has not run).  Returns True when all are done."""
+        if self.O is None:
+            self.O = np.full((self.N * self.k, self.H), np.nan, dtype=np.float64)
+        budget = self.n_units if max_units is None else max_units
+        u = self.next_unit
+        while u < self.n_units and budget > 0:
+            if not self.executed[u]:
+                self._execute(u)
+                budget -= 1
+            u += 1
+        self._advance()
+        return self.next_unit == self.n_units
+
+    def run_units(self, ids) -> bool:
+        """Execute the listed units in the given order (a policy's choice: any units that have not
+        run yet).  The paper lets user-defined policies pick which experts run (sections "Challenges
+        and Design Decisions" and "System Architecture"); a token counts as complete only once all k
+        of its assignments have run ("Top-k expert selection" in the former section)."""
+        for u in ids:
+            assert 0 <= u < self.n_units and not self.executed[u]
+            self._execute(int(u))
+        self._advance()
         return self.next_unit == self.n_units
 
     def y(self, tokens=None):

@@ -359,6 +359,55 @@ def test_only_complete_tokens_are_combined_and_ls_finishes_first():
     assert np.array_equal(y_mid[inp.prio != 0], y_end[inp.prio != 0])
 
 
+def complete_from_first_principles(idx, prio, E, chunk_rows, executed_chunks):
+    """Which tokens are complete when the chunks in `executed_chunks` (a set of (expert, class,
+    chunk number inside that expert's class queue)) have run, derived from the routing alone:
+    assignment (n, j) to expert e sits at position #{n' < n of the same class that chose e} of the
+    (e, class) FIFO queue, i.e. in chunk position // chunk_rows."""
+    N, k = idx.shape
+    comp = np.ones(N, dtype=bool)
+    seen = np.zeros((E, 2), dtype=np.int64)
+    for n in range(N):
+        c = 0 if prio[n] else 1
+        for e in sorted(set(int(v) for v in idx[n])):
+            if (e, c, seen[e, c] // chunk_rows) not in executed_chunks:
+                comp[n] = False
+            seen[e, c] += 1
+    return comp
+
+
+@pytest.mark.parametrize("seed", [3, 4, 5])
+def test_policy_chosen_unit_order_completeness_and_exactness(seed):
+    cfg = small_cfg(N=40, n_ls=11, E=6, k=3, chunk_rows=3, seed=100 + seed)
+    inp = wl.make_inputs(cfg)
+    full = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    full.run()
+    y_full, _ = full.y()
+    rng = np.random.default_rng(seed)
+    lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    order = rng.permutation(lay.n_units)
+    first, rest = order[: lay.n_units // 2], order[lay.n_units // 2:]
+    lay.run_units(first)
+    # chunk number of a unit inside its (expert, class) queue, from the unit list's own row ranges
+    chunks = set()
+    for u in first:
+        e, c, r0, _rows = (int(v) for v in lay.units[u])
+        start = int(lay.off[2 * e + c])
+        assert (r0 - start) % cfg.chunk_rows == 0
+        chunks.add((e, c, (r0 - start) // cfg.chunk_rows))
+    y_mid, comp = lay.y()
+    assert np.array_equal(comp, complete_from_first_principles(lay.idx, inp.prio, cfg.E, cfg.chunk_rows, chunks))
+    assert 0 < comp.sum() < cfg.N                                   # the case has both kinds of token
+    assert np.array_equal(y_mid[comp], y_full[comp]) and np.isnan(y_mid[~comp]).all()
+    # the cursor is the first unit that has not run; run() skips what a policy already ran
+    assert lay.next_unit == min(set(range(lay.n_units)) - set(int(u) for u in first))
+    lay.run(2)
+    lay.run_units([u for u in rest if not lay.executed[u]][::-1])
+    assert lay.next_unit == lay.n_units and np.all(lay.executed == 1)
+    y_end, comp = lay.y()
+    assert comp.all() and np.array_equal(y_end, y_full)
+
+
 def test_workload_recipes():
     c5 = wl.CONFIGS["cfg5"]
     b = wl.make_bias(c5)
