@@ -9,7 +9,8 @@
  *
  * One layer-batch goes through
  *
- *     moe_route -> moe_permute -> moe_expert_run (any number of calls) -> moe_combine
+ *     moe_route -> moe_permute -> moe_expert_run / moe_expert_run_units (any number of calls)
+ *               -> moe_combine / moe_combine_complete
  *
  * Every return of moe_expert_run is a preemption point: the caller may run other contexts (for
  * instance a newly arrived LS batch) before calling it again with the saved cursor.
@@ -157,16 +158,27 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
 int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void *stream);
 
 /* Expert work, resumable (Sec. 3.1 "Top-k expert selection"; Introduction, contribution 3).
- * Executes units [cursor->next_unit, min(next_unit + max_units, n_units)) : for each row r of a
- * unit of expert e, with token n = perm[r] / k,
+ * Executes the next max_units units that have not run yet, in list order, starting at
+ * cursor->next_unit (the first unit that has not run): for each row r of a unit of expert e, with
+ * token n = perm[r] / k,
  *     act[r,:] = silu(W1[e] x[n,:]) (.) (W3[e] x[n,:]),   out[r,:] = W2[e] act[r,:]
  * and advances *cursor ([host], in/out).  max_units = UINT32_MAX runs to the end.  x and w must be
  * the tensors given to moe_route, unchanged.  *cursor must be the value last returned for this
  * context (MOE_E_ARG otherwise): no unit is ever executed twice.  Results do not depend on how
  * the unit list is split into calls, bit for bit.
- * Returns MOE_OK while units remain, MOE_DONE when the list is exhausted. */
+ * Returns MOE_OK while units remain, MOE_DONE when every unit has run. */
 int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t max_units,
                        moe_cursor *cursor, void *stream);
+
+/* Expert work in an order the caller chooses (Sec. 3.1 "User-defined scheduling policies", Sec. 3.2:
+ * policies at the granularity of experts, e.g. selective expert execution).  unit_ids [host]
+ * uint32[n]: indices into the context's unit list (moe_units), distinct, each not yet executed; any
+ * order.  The arithmetic per row is that of moe_expert_run, bit for bit.  On a bad id (out of range,
+ * repeated, already executed) nothing runs and MOE_E_ARG is returned.  *cursor ([host], may be
+ * NULL) receives the context's cursor afterwards: next_unit = first unit that has not run, so
+ * moe_expert_run can carry on from it.  Returns MOE_OK while units remain, MOE_DONE when all ran. */
+int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, const uint32_t *unit_ids,
+                             uint32_t n, moe_cursor *cursor, void *stream);
 
 /* Gate-weighted combine of complete tokens (Sec. 3.1: only fully processed tokens contribute to
  * the next layer's hidden state):
@@ -176,6 +188,14 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
  * MOE_CLASS_BE or MOE_CLASS_ALL; rows of other tokens are left untouched.  If a selected class
  * still has unexecuted units the call fails with MOE_E_INCOMPLETE. */
 int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream);
+
+/* Combine of whatever is complete (Sec. 3.1 "Top-k expert selection": fully and partially processed
+ * tokens are told apart, only complete ones contribute).  A token is complete when the units holding
+ * all k of its assignments have been executed, in whatever order and by whichever call.  Rows of y
+ * ([device] [n_tokens,H]) of complete tokens are written exactly as moe_combine writes them; rows of
+ * the other tokens are left untouched.  complete ([device] uint8[n_tokens], may be NULL) receives 1
+ * for complete tokens, 0 for the others.  Never fails with MOE_E_INCOMPLETE. */
+int32_t moe_combine_complete(moe_ctx *ctx, void *y, uint8_t *complete, void *stream);
 
 /* Read-back for tests and schedulers: a [device] pointer into the workspace and its size in bytes
  * for the current layer-batch.  Valid until the next moe_route on this context. */

@@ -81,6 +81,9 @@ def lib():
         L.moe_expert_run.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.c_uint32,
                                      C.POINTER(MoeCursor), C.c_void_p]
         L.moe_combine.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.moe_expert_run_units.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.POINTER(C.c_uint32),
+                                           C.c_uint32, C.POINTER(MoeCursor), C.c_void_p]
+        L.moe_combine_complete.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.moe_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
         L.moe_units.argtypes = [C.c_void_p, C.POINTER(MoeUnit), C.c_uint32, C.POINTER(C.c_uint32)]
         L.moe_plan_units.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(MoeUnit), C.c_uint32,
@@ -88,7 +91,7 @@ def lib():
         L.moe_pack_weights.argtypes = [C.POINTER(MoeConfig), C.POINTER(MoeWeights), C.POINTER(MoeWeights), C.c_void_p]
         L.moe_profile.argtypes = [C.c_void_p, C.c_int32]
         L.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
-        for f in ("moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
+        for f in ("moe_expert_run_units", "moe_combine_complete", "moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
                   "moe_get", "moe_units", "moe_plan_units"):
             getattr(L, f).restype = C.c_int32
         # include/qsched.h
@@ -204,6 +207,20 @@ class Context:
 
     def combine(self, y, class_mask: int = MOE_CLASS_ALL) -> int:
         return _check(lib().moe_combine(self.h, _ptr(y), class_mask, _stream()))
+
+    def expert_run_units(self, x, w: MoeWeights, unit_ids) -> int:
+        """Execute the listed units (indices into units()) in the given order; updates self.cursor."""
+        ids = [int(u) for u in unit_ids]
+        arr = (C.c_uint32 * max(1, len(ids)))(*ids)
+        return _check(lib().moe_expert_run_units(self.h, _ptr(x), C.byref(w), arr, len(ids), C.byref(self.cursor),
+                                                 _stream()))
+
+    def combine_complete(self, y, complete=None) -> int:
+        """Write the rows of y of every token whose k assignments have all been executed; `complete`
+        (uint8 tensor [N], optional) receives the mask."""
+        if complete is not None and complete.element_size() != 1:
+            raise TypeError("complete must be a uint8 tensor")
+        return _check(lib().moe_combine_complete(self.h, _ptr(y), _ptr(complete), _stream()))
 
     def profile(self, enable: bool) -> None:
         _check(lib().moe_profile(self.h, 1 if enable else 0))

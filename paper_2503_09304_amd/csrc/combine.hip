@@ -5,26 +5,43 @@
 // loads along the hidden dimension.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "qmoe_internal.h"
 
 namespace qmoe {
 namespace {
 
+// done == nullptr: tokens are selected by class (the host has checked that the class is finished).
+// done != nullptr: a token is selected when done[] is set for all k of its sorted positions;
+// complete[n] (if given) reports the selection.
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ out, const float *__restrict__ topk_w,
                                                     const int32_t *__restrict__ inv, const uint8_t *__restrict__ cls,
+                                                    const uint8_t *__restrict__ done, uint8_t *__restrict__ complete,
                                                     void *__restrict__ y, int N, int H, int k, int class_mask) {
     const int n = blockIdx.x;
     if (n >= N) return;
-    const int bit = cls[n] == 0 ? MOE_CLASS_LS : MOE_CLASS_BE;
-    if (!(class_mask & bit)) return;
+    if (done == nullptr) {
+        const int bit = cls[n] == 0 ? MOE_CLASS_LS : MOE_CLASS_BE;
+        if (!(class_mask & bit)) return;
+    }
     __shared__ float sw[kMaxTopK];
     __shared__ int32_t sp[kMaxTopK];
+    __shared__ int missing;
+    if (threadIdx.x == 0) missing = 0;
+    __syncthreads();
     if (threadIdx.x < k) {
+        const int32_t p = inv[(long)n * k + threadIdx.x];
         sw[threadIdx.x] = topk_w[(long)n * k + threadIdx.x];
-        sp[threadIdx.x] = inv[(long)n * k + threadIdx.x];
+        sp[threadIdx.x] = p;
+        if (done != nullptr && done[p] == 0) missing = 1;     // any writer stores the same value
     }
     __syncthreads();
+    if (done != nullptr) {
+        if (complete != nullptr && threadIdx.x == 0) complete[n] = missing ? 0 : 1;
+        if (missing) return;
+    }
     if ((H & 3) == 0) {
         for (int h = threadIdx.x * 4; h < H; h += 1024) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -53,17 +70,51 @@ __global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ ou
     }
 }
 
+// done[row] = 1 for the rows of up to kMaxSegs row ranges: one workgroup per range.
+struct MarkArgs {
+    int n;
+    Seg seg[kMaxSegs];
+};
+
+__global__ __launch_bounds__(256) void mark_rows(const MarkArgs m, uint8_t *__restrict__ done) {
+    const Seg g = m.seg[blockIdx.x];
+    for (int r = threadIdx.x; r < g.rows; r += 256) done[g.row0 + r] = 1;
+}
+
+__global__ __launch_bounds__(256) void clear_bytes(uint8_t *__restrict__ p, long n) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = 0;
+}
+
 }  // namespace
 
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s) {
     if (a.N <= 0) return hipSuccess;
     if (a.dtype == MOE_BF16)
-        hipLaunchKernelGGL(combine_rows<true>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.y, a.N, a.H,
-                           a.k, a.class_mask);
+        hipLaunchKernelGGL(combine_rows<true>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.done,
+                           a.complete, a.y, a.N, a.H, a.k, a.class_mask);
     else
-        hipLaunchKernelGGL(combine_rows<false>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.y, a.N, a.H,
-                           a.k, a.class_mask);
+        hipLaunchKernelGGL(combine_rows<false>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.done,
+                           a.complete, a.y, a.N, a.H, a.k, a.class_mask);
     return hipGetLastError();
+}
+
+hipError_t launch_clear_done(uint8_t *done, long n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<long>((n + 255) / 256, 1024);
+    hipLaunchKernelGGL(clear_bytes, dim3(blocks), dim3(256), 0, s, done, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_mark_done(const Seg *segs, int n, uint8_t *done, hipStream_t s) {
+    for (int i = 0; i < n; i += kMaxSegs) {
+        MarkArgs m{};
+        m.n = std::min(kMaxSegs, n - i);
+        std::copy(segs + i, segs + i + m.n, m.seg);
+        hipLaunchKernelGGL(mark_rows, dim3(m.n), dim3(256), 0, s, m, done);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace qmoe

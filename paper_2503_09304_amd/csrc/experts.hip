@@ -2,7 +2,8 @@
 //     act[r,:] = silu(W1[e] x[n,:]) (.) (W3[e] x[n,:])        ("gate-up" kernel, SwiGLU fused)
 //     out[r,:] = W2[e] act[r,:]                               ("down" kernel)
 // Independent per-expert execution over the per-expert queues (Introduction, "Novel MoE Layer
-// Design"; Sec. 3.3), one call covering the units [u0, u0+nu) handed over by the cursor.
+// Design"; Sec. 3.3), one call covering the row segments (or the range [u0, u0+nu) of the device unit
+// list) handed over by the host.
 #include <hip/hip_runtime.h>
 
 #include "experts_common.h"
@@ -23,7 +24,7 @@ void Profiler::begin(int kind, hipStream_t s) {
 void Profiler::end(hipStream_t s) { (void)hipEventRecord(spans.back().b, s); }
 
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s) {
-    if (a.nu == 0) return hipSuccess;
+    if (a.nu == 0 && a.nseg == 0) return hipSuccess;
     KArgs gu{};
     gu.a_src = a.x; gu.perm = a.perm; gu.b0 = a.W1; gu.b1 = a.W3; gu.dst = a.act; gu.units = a.units;
     gu.b_estride = (long)a.F * a.H; gu.lda = a.H; gu.K = a.H; gu.ncols = a.F; gu.ldd = a.F; gu.kdiv = a.k;

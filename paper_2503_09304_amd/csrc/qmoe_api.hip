@@ -54,7 +54,7 @@ bool config_ok(const moe_config *c, const char **why) {
 
 // Offsets of the workspace regions, computed the same way for sizing and for carving.
 struct Layout {
-    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, units, wgt, act, out, partial, total;
+    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, units, wgt, act, out, partial, total;
     bool has_partial;
     uint32_t max_units;
 };
@@ -84,6 +84,7 @@ Layout make_layout(const moe_config &c) {
     L.rank = take(A * 4);
     L.blockoff = take((nblocks ? nblocks : 1) * 2 * E * 4);
     L.cls = take(N ? N : 1);
+    L.done = take(A ? A : 1);           // completion flag per sorted row (moe_combine_complete)
     L.units = take((size_t)L.max_units * sizeof(moe_unit));
     L.wgt = take(((E + 15) / 16 * 16) * (size_t)c.H * 2);
     L.act = take(A * (size_t)c.F * es);
@@ -105,8 +106,12 @@ struct moe_ctx {
     char *ws;
     int state;
     int32_t N;
-    uint32_t next_unit, n_units, n_ls_units;
+    uint32_t next_unit, n_units, n_ls_units;   // next_unit: first unit that has not run
+    uint32_t n_done, n_ls_done;                // executed units, and how many of them are LS units
     std::vector<moe_unit> units;
+    std::vector<uint8_t> executed;             // per unit
+    std::vector<uint32_t> unmarked;            // executed units whose rows are not yet flagged on the device
+    bool done_valid;                           // the device flags of this layer-batch have been cleared
     std::vector<int32_t> cnt;
     int32_t *pinned;  // 2E counts + 1 unit count, pinned host memory (allocated at first route)
     const void *x;
@@ -196,7 +201,8 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->ws = static_cast<char *>(workspace);
     c->state = ST_CREATED;
     c->N = 0;
-    c->next_unit = c->n_units = c->n_ls_units = 0;
+    c->next_unit = c->n_units = c->n_ls_units = c->n_done = c->n_ls_done = 0;
+    c->done_valid = false;
     c->pinned = nullptr;
     c->prof_on = false;
     c->x = nullptr;
@@ -243,8 +249,11 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     ctx->x = x;
     ctx->w = *w;
     ctx->state = ST_ROUTED;
-    ctx->next_unit = ctx->n_units = ctx->n_ls_units = 0;
+    ctx->next_unit = ctx->n_units = ctx->n_ls_units = ctx->n_done = ctx->n_ls_done = 0;
     ctx->units.clear();
+    ctx->executed.clear();
+    ctx->unmarked.clear();
+    ctx->done_valid = false;
     ctx->cnt.assign(2 * (size_t)ctx->cfg.E, 0);
     return MOE_OK;
 }
@@ -295,82 +304,143 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
     ctx->n_ls_units = 0;
     for (const moe_unit &u : ctx->units) ctx->n_ls_units += u.cls == 0;
     ctx->next_unit = 0;
+    ctx->n_done = ctx->n_ls_done = 0;
+    ctx->executed.assign(n, 0);
+    ctx->unmarked.clear();
+    ctx->done_valid = false;
     ctx->state = ST_PERMUTED;
     cursor->next_unit = 0;
     cursor->n_units = n;
     return MOE_OK;
 }
 
+// Launches the expert kernels for the listed units (already validated: in range, distinct, not
+// yet executed) and books them as executed.
+static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
+                             hipStream_t stream, const char *who) {
+    if (ids.empty()) return MOE_OK;
+    qmoe::ExpertArgs a{};
+    a.x = x; a.W1 = w->W1; a.W3 = w->W3; a.W2 = w->W2;
+    a.perm = at<int32_t>(ctx, ctx->lay.perm);
+    a.units = at<moe_unit>(ctx, ctx->lay.units);
+    a.act = at<void>(ctx, ctx->lay.act);
+    a.out = at<float>(ctx, ctx->lay.out);
+    a.H = ctx->cfg.H; a.F = ctx->cfg.F; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
+    a.prof = ctx->prof_on ? &ctx->prof : nullptr;
+    a.packed = w->layout == MOE_W_PACKED;
+    a.ksplit = ctx->lay.has_partial ? 4 : 1;
+    a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
+    a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
+    const moe_unit *un = ctx->units.data();
+    bool contiguous = true;                       // ids = u0, u0+1, ..., a range of the device unit list
+    for (size_t i = 1; i < ids.size(); ++i) contiguous = contiguous && ids[i] == ids[i - 1] + 1;
+    hipError_t e = hipSuccess;
+    if (ctx->cfg.dtype == MOE_BF16) {
+        // Row segments: units sorted by (expert, row), row-adjacent units of one expert (its LS part
+        // and the start of its BE part, or consecutive chunks) merged while they fit 256 rows, so
+        // that one pass over the expert's weights serves them all.  Which rows share a workgroup
+        // never changes what is computed for a row.
+        std::vector<uint32_t> idx(ids);
+        std::stable_sort(idx.begin(), idx.end(), [un](uint32_t p, uint32_t q) {
+            if (un[p].expert != un[q].expert) return un[p].expert < un[q].expert;
+            return un[p].row0 < un[q].row0;
+        });
+        std::vector<qmoe::Seg> segs;
+        for (uint32_t i : idx) {
+            const moe_unit &u = un[i];
+            if (!segs.empty()) {
+                qmoe::Seg &b = segs.back();
+                if (b.expert == (uint16_t)u.expert && b.row0 + b.rows == (uint32_t)u.row0 && b.rows + u.rows <= 256) {
+                    b.rows = (uint16_t)(b.rows + u.rows);
+                    continue;
+                }
+            }
+            segs.push_back(qmoe::Seg{(uint32_t)u.row0, (uint16_t)u.rows, (uint16_t)u.expert});
+        }
+        if (segs.size() > (size_t)qmoe::kMaxSegs && contiguous) {
+            // too many segments for the kernel arguments: the launch reads the device unit list
+            a.u0 = ids.front(); a.nu = (uint32_t)ids.size();
+            a.max_rows = 0;
+            for (uint32_t i : ids) a.max_rows = std::max(a.max_rows, (int)un[i].rows);
+            a.segs = nullptr; a.nseg = 0;
+            e = qmoe::launch_experts(a, stream);
+        } else {
+            for (size_t s0 = 0; s0 < segs.size() && e == hipSuccess; s0 += qmoe::kMaxSegs) {
+                const size_t cnt = std::min(segs.size() - s0, (size_t)qmoe::kMaxSegs);
+                a.segs = segs.data() + s0; a.nseg = (int)cnt;
+                a.u0 = 0; a.nu = 0;
+                a.max_rows = 0;
+                for (size_t i = 0; i < cnt; ++i) a.max_rows = std::max(a.max_rows, (int)segs[s0 + i].rows);
+                e = qmoe::launch_experts(a, stream);
+            }
+        }
+    } else {
+        // fp32 kernels walk ranges of the device unit list: one launch per run of consecutive ids
+        for (size_t i = 0; i < ids.size() && e == hipSuccess;) {
+            size_t j = i + 1;
+            while (j < ids.size() && ids[j] == ids[j - 1] + 1) ++j;
+            a.u0 = ids[i]; a.nu = (uint32_t)(j - i);
+            a.max_rows = 0;
+            for (size_t q = i; q < j; ++q) a.max_rows = std::max(a.max_rows, (int)un[ids[q]].rows);
+            a.segs = nullptr; a.nseg = 0;
+            e = qmoe::launch_experts(a, stream);
+            i = j;
+        }
+    }
+    if (e != hipSuccess) return hip_fail(e, who);
+    for (uint32_t i : ids) {
+        ctx->executed[i] = 1;
+        ctx->n_done += 1;
+        ctx->n_ls_done += un[i].cls == 0;
+        ctx->unmarked.push_back(i);
+    }
+    while (ctx->next_unit < ctx->n_units && ctx->executed[ctx->next_unit]) ++ctx->next_unit;
+    return MOE_OK;
+}
+
+static int32_t check_run_args(moe_ctx *ctx, const void *x, const moe_weights *w, const char *who) {
+    if (!ctx) return fail(MOE_E_ARG, "%s: null context", who);
+    if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "%s: call moe_permute first", who);
+    if (!w || (ctx->N > 0 && !x)) return fail(MOE_E_ARG, "%s: null x or weights", who);
+    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout)
+        return fail(MOE_E_ARG, "%s: x and weights must be the tensors given to moe_route", who);
+    return MOE_OK;
+}
+
 int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t max_units, moe_cursor *cursor,
                        void *stream) {
-    if (!ctx) return fail(MOE_E_ARG, "moe_expert_run: null context");
-    if (!cursor) return fail(MOE_E_ARG, "moe_expert_run: null cursor");
-    if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_expert_run: call moe_permute first");
+    if (ctx && !cursor) return fail(MOE_E_ARG, "moe_expert_run: null cursor");
+    int32_t rc = check_run_args(ctx, x, w, "moe_expert_run");
+    if (rc != MOE_OK) return rc;
     if (cursor->n_units != ctx->n_units || cursor->next_unit != ctx->next_unit)
         return fail(MOE_E_ARG, "moe_expert_run: cursor {%u,%u} is not this context's {%u,%u}", cursor->next_unit,
                     cursor->n_units, ctx->next_unit, ctx->n_units);
-    if (!w || (ctx->N > 0 && !x)) return fail(MOE_E_ARG, "moe_expert_run: null x or weights");
-    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout)
-        return fail(MOE_E_ARG, "moe_expert_run: x and weights must be the tensors given to moe_route");
-    const uint32_t u0 = ctx->next_unit;
-    const uint32_t left = ctx->n_units - u0;
-    const uint32_t nu = max_units < left ? max_units : left;
-    if (nu > 0) {
-        qmoe::ExpertArgs a{};
-        a.x = x; a.W1 = w->W1; a.W3 = w->W3; a.W2 = w->W2;
-        a.perm = at<int32_t>(ctx, ctx->lay.perm);
-        a.units = at<moe_unit>(ctx, ctx->lay.units);
-        a.act = at<void>(ctx, ctx->lay.act);
-        a.out = at<float>(ctx, ctx->lay.out);
-        a.H = ctx->cfg.H; a.F = ctx->cfg.F; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
-        a.u0 = u0; a.nu = nu;
-        a.prof = ctx->prof_on ? &ctx->prof : nullptr;
-        a.packed = w->layout == MOE_W_PACKED;
-        a.ksplit = ctx->lay.has_partial ? 4 : 1;
-        a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
-        a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
-        // Row segments of this launch: units sorted by (expert, row), row-adjacent units of one
-        // expert (its LS part and the start of its BE part, or consecutive chunks) merged while they
-        // fit 256 rows, so that one pass over the expert's weights serves them all.  Which rows
-        // share a workgroup never changes what is computed for a row.
-        std::vector<qmoe::Seg> segs;
-        a.max_rows = 0;
-        if (ctx->cfg.dtype == MOE_BF16) {
-            std::vector<uint32_t> idx(nu);
-            for (uint32_t i = 0; i < nu; ++i) idx[i] = u0 + i;
-            const moe_unit *un = ctx->units.data();
-            std::stable_sort(idx.begin(), idx.end(), [un](uint32_t x, uint32_t y) {
-                if (un[x].expert != un[y].expert) return un[x].expert < un[y].expert;
-                return un[x].row0 < un[y].row0;
-            });
-            for (uint32_t i : idx) {
-                const moe_unit &u = un[i];
-                if (!segs.empty()) {
-                    qmoe::Seg &b = segs.back();
-                    if (b.expert == (uint16_t)u.expert && b.row0 + b.rows == (uint32_t)u.row0 && b.rows + u.rows <= 256) {
-                        b.rows = (uint16_t)(b.rows + u.rows);
-                        continue;
-                    }
-                }
-                segs.push_back(qmoe::Seg{(uint32_t)u.row0, (uint16_t)u.rows, (uint16_t)u.expert});
-            }
-            if (segs.size() > (size_t)qmoe::kMaxSegs) segs.clear();
-        }
-        if (!segs.empty()) {
-            for (const qmoe::Seg &g : segs) if (g.rows > a.max_rows) a.max_rows = g.rows;
-            a.segs = segs.data();
-            a.nseg = (int)segs.size();
-        } else {
-            for (uint32_t u = u0; u < u0 + nu; ++u) if (ctx->units[u].rows > a.max_rows) a.max_rows = ctx->units[u].rows;
-            a.segs = nullptr;
-            a.nseg = 0;
-        }
-        hipError_t e = qmoe::launch_experts(a, (hipStream_t)stream);
-        if (e != hipSuccess) return hip_fail(e, "moe_expert_run: launch");
-    }
-    ctx->next_unit = u0 + nu;
+    std::vector<uint32_t> ids;
+    for (uint32_t u = ctx->next_unit; u < ctx->n_units && ids.size() < (size_t)max_units; ++u)
+        if (!ctx->executed[u]) ids.push_back(u);
+    rc = run_unit_list(ctx, x, w, ids, (hipStream_t)stream, "moe_expert_run: launch");
+    if (rc != MOE_OK) return rc;
     cursor->next_unit = ctx->next_unit;
-    return ctx->next_unit == ctx->n_units ? MOE_DONE : MOE_OK;
+    return ctx->n_done == ctx->n_units ? MOE_DONE : MOE_OK;
+}
+
+int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, const uint32_t *unit_ids, uint32_t n,
+                             moe_cursor *cursor, void *stream) {
+    int32_t rc = check_run_args(ctx, x, w, "moe_expert_run_units");
+    if (rc != MOE_OK) return rc;
+    if (n > 0 && !unit_ids) return fail(MOE_E_ARG, "moe_expert_run_units: null unit_ids");
+    std::vector<uint32_t> ids(unit_ids, unit_ids + n);
+    std::vector<uint8_t> seen(ctx->n_units, 0);
+    for (uint32_t u : ids) {
+        if (u >= ctx->n_units) return fail(MOE_E_ARG, "moe_expert_run_units: unit %u out of range (%u units)", u, ctx->n_units);
+        if (ctx->executed[u]) return fail(MOE_E_ARG, "moe_expert_run_units: unit %u has already been executed", u);
+        if (seen[u]) return fail(MOE_E_ARG, "moe_expert_run_units: unit %u listed twice", u);
+        seen[u] = 1;
+    }
+    rc = run_unit_list(ctx, x, w, ids, (hipStream_t)stream, "moe_expert_run_units: launch");
+    if (rc != MOE_OK) return rc;
+    if (cursor) { cursor->next_unit = ctx->next_unit; cursor->n_units = ctx->n_units; }
+    return ctx->n_done == ctx->n_units ? MOE_DONE : MOE_OK;
 }
 
 int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
@@ -378,10 +448,12 @@ int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_combine: call moe_permute first");
     if (class_mask < 1 || class_mask > 3) return fail(MOE_E_ARG, "moe_combine: class_mask must be 1, 2 or 3");
     if (ctx->N > 0 && !y) return fail(MOE_E_ARG, "moe_combine: null y");
-    if ((class_mask & MOE_CLASS_LS) && ctx->next_unit < ctx->n_ls_units)
-        return fail(MOE_E_INCOMPLETE, "moe_combine: LS tokens still have %u unexecuted units", ctx->n_ls_units - ctx->next_unit);
-    if ((class_mask & MOE_CLASS_BE) && ctx->next_unit < ctx->n_units)
-        return fail(MOE_E_INCOMPLETE, "moe_combine: BE tokens still have %u unexecuted units", ctx->n_units - ctx->next_unit);
+    const uint32_t ls_left = ctx->n_ls_units - ctx->n_ls_done;
+    const uint32_t be_left = (ctx->n_units - ctx->n_ls_units) - (ctx->n_done - ctx->n_ls_done);
+    if ((class_mask & MOE_CLASS_LS) && ls_left)
+        return fail(MOE_E_INCOMPLETE, "moe_combine: LS tokens still have %u unexecuted units", ls_left);
+    if ((class_mask & MOE_CLASS_BE) && be_left)
+        return fail(MOE_E_INCOMPLETE, "moe_combine: BE tokens still have %u unexecuted units", be_left);
     if (ctx->N == 0) return MOE_OK;
     qmoe::CombineArgs a{};
     a.out = at<float>(ctx, ctx->lay.out);
@@ -392,6 +464,44 @@ int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
     a.N = ctx->N; a.H = ctx->cfg.H; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype; a.class_mask = class_mask;
     hipError_t e = qmoe::launch_combine(a, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "moe_combine: launch");
+    return MOE_OK;
+}
+
+int32_t moe_combine_complete(moe_ctx *ctx, void *y, uint8_t *complete, void *stream) {
+    if (!ctx) return fail(MOE_E_ARG, "moe_combine_complete: null context");
+    if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_combine_complete: call moe_permute first");
+    if (ctx->N > 0 && !y) return fail(MOE_E_ARG, "moe_combine_complete: null y");
+    if (ctx->N == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t *done = at<uint8_t>(ctx, ctx->lay.done);
+    // Bring the device's per-row completion flags up to date with what has been executed since
+    // the last call (they are not maintained on the moe_expert_run path, which does not need them).
+    hipError_t e = hipSuccess;
+    if (!ctx->done_valid) {
+        e = qmoe::launch_clear_done(done, (long)ctx->N * ctx->cfg.k, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_combine_complete: clearing the flags");
+        ctx->done_valid = true;
+    }
+    if (!ctx->unmarked.empty()) {
+        std::vector<qmoe::Seg> segs;
+        segs.reserve(ctx->unmarked.size());
+        for (uint32_t u : ctx->unmarked)
+            segs.push_back(qmoe::Seg{(uint32_t)ctx->units[u].row0, (uint16_t)ctx->units[u].rows, (uint16_t)ctx->units[u].expert});
+        e = qmoe::launch_mark_done(segs.data(), (int)segs.size(), done, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_combine_complete: setting the flags");
+        ctx->unmarked.clear();
+    }
+    qmoe::CombineArgs a{};
+    a.out = at<float>(ctx, ctx->lay.out);
+    a.topk_w = at<float>(ctx, ctx->lay.topk_w);
+    a.inv = at<int32_t>(ctx, ctx->lay.inv);
+    a.cls = at<uint8_t>(ctx, ctx->lay.cls);
+    a.done = done;
+    a.complete = complete;
+    a.y = y;
+    a.N = ctx->N; a.H = ctx->cfg.H; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype; a.class_mask = MOE_CLASS_ALL;
+    e = qmoe::launch_combine(a, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_combine_complete: launch");
     return MOE_OK;
 }
 

@@ -96,9 +96,14 @@ struct CombineArgs {
     const float *topk_w;   // [N,k]
     const int32_t *inv;    // [A]
     const uint8_t *cls;    // [N]
+    const uint8_t *done;   // [A] per sorted row, or nullptr: select by class_mask
+    uint8_t *complete;     // [N] out (with done), or nullptr
     void *y;               // [N,H] dtype
     int N, H, k, dtype, class_mask;
 };
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
+// Completion flags per sorted row (used by moe_combine_complete): clear all, set the rows of segments.
+hipError_t launch_clear_done(uint8_t *done, long n, hipStream_t s);
+hipError_t launch_mark_done(const Seg *segs, int n, uint8_t *done, hipStream_t s);
 
 }  // namespace qmoe
