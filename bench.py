@@ -35,18 +35,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def gate_up_bytes(cfg, counts, es):
+def gate_up_bytes(cfg, counts, es, ws):
     """Algorithmic HBM bytes of the gate-up launch of a run-to-completion call: W1 and W3 of every
     expert that has rows, once (the launch merges an expert's LS and BE rows into one pass over
-    its weights), the gathered x rows once, the activation written once."""
+    its weights; ws bytes per weight element), the gathered x rows once, the activation written once."""
     touched = int((counts.sum(1) > 0).sum())
-    return touched * 2 * cfg.F * cfg.H * es + cfg.A * cfg.H * es + cfg.A * cfg.F * es
+    return int(touched * 2 * cfg.F * cfg.H * ws) + cfg.A * cfg.H * es + cfg.A * cfg.F * es
 
 
-def down_bytes(cfg, counts, es, ksplit):
+def down_bytes(cfg, counts, es, ws, ksplit):
     touched = int((counts.sum(1) > 0).sum())
     planes = 4 * cfg.A * cfg.H * 4 * 2 if ksplit == 4 else 0     # partial planes written, then read
-    return touched * cfg.H * cfg.F * es + cfg.A * cfg.F * es + cfg.A * cfg.H * 4 + planes
+    return int(touched * cfg.H * cfg.F * ws) + cfg.A * cfg.F * es + cfg.A * cfg.H * 4 + planes
 
 
 def pct(v, p):
@@ -214,6 +214,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rowmajor", action="store_true", help="keep the weights row-major (default: packed at load)")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "mxfp4"],
+                    help="expert weight format: bf16 (the headline workload) or 4-bit microscaling FP4")
     ap.add_argument("--latency-trials", type=int, default=40,
                     help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
     ap.add_argument("--units-per-call", type=int, default=1)
@@ -242,11 +244,21 @@ def main() -> int:
     es = wl.elem_bytes(cfg)
     log("workload", wl.describe(cfg))
     t0 = time.time()
-    inp = wl.make_inputs(cfg)
+    mx = args.weights == "mxfp4"
+    ws = 0.5 + 1.0 / 32 if mx else es      # bytes per expert-weight element (4-bit code + its share of a scale byte)
+    if mx:
+        from gpu_util import DevWeightsMX
+        w4 = wl.make_weights_mxfp4(cfg)
+        inp = wl.make_inputs(cfg, weights={})
+    else:
+        inp = wl.make_inputs(cfg)
     log(f"inputs drawn in {time.time() - t0:.1f}s")
-    dw = DevWeights(inp.w)
-    if not args.rowmajor:
-        dw = dw.packed()          # one-time re-layout at model load, outside the timed region
+    if mx:
+        dw = DevWeightsMX(w4).packed()
+    else:
+        dw = DevWeights(inp.w)
+        if not args.rowmajor:
+            dw = dw.packed()      # one-time re-layout at model load, outside the timed region
     g = GpuLayer(inp, dw)
     torch.cuda.synchronize()
     if args.calib_copy:
@@ -295,8 +307,8 @@ def main() -> int:
     gu_ms, gu_n = prof["gate_up"]
     dn_ms = prof["down"][0] + prof["down_reduce"][0]
     gu_avg_ms = gu_ms / max(gu_n, 1)
-    gub = gate_up_bytes(cfg, counts, es)
-    dnb = down_bytes(cfg, counts, es, ksplit)
+    gub = gate_up_bytes(cfg, counts, es, ws)
+    dnb = down_bytes(cfg, counts, es, ws, ksplit)
     flops = wl.flops(cfg)
     gu_flops = 4.0 * cfg.A * cfg.H * cfg.F
     hbm_bound = (gub / (HBM_PEAK_GBS * 1e9)) >= (gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
@@ -308,7 +320,7 @@ def main() -> int:
         achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.rowmajor else None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name + ("_mxfp4" if mx else "")) if not args.rowmajor else None
     roof.update({"kernel": "expert_bf16 gate-up (W1,W3 GEMM + SwiGLU)", "avg_launch_ms": round(gu_avg_ms, 4),
                  "launches": gu_n, "algorithmic_bytes_per_launch": int(gub),
                  "algorithmic_flops_per_launch": gu_flops,
@@ -318,7 +330,7 @@ def main() -> int:
 
     # ---- LS latency while a long BE batch is in flight (Mixtral weights)
     lat = None
-    if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16":
+    if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx:
         lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead)
         log("LS latency under BE load:", json.dumps(lat))
 
@@ -329,7 +341,8 @@ def main() -> int:
         ns = min(args.cpu_sample_tokens, cfg.N)
         xs, ps = inp.x[:ns], inp.prio[:ns]
         t0 = time.perf_counter()
-        lay = oracle.OracleLayer(xs, inp.w, ps, inp.bias, cfg.k, cfg.chunk_rows)
+        w_or = oracle.mxfp4_weights_as_bf16(w4) if mx else inp.w
+        lay = oracle.OracleLayer(xs, w_or, ps, inp.bias, cfg.k, cfg.chunk_rows)
         lay.run()
         y_ref, _ = lay.y()
         t_cpu = time.perf_counter() - t0
@@ -354,7 +367,8 @@ def main() -> int:
                                f"chunk_rows={cfg.chunk_rows} seed={cfg.seed}",
                    "call": "one run-to-completion moe_expert_run (LS units first in the unit list; an expert's "
                            "LS and BE rows share one pass over its weights)",
-                   "weights": "row-major" if args.rowmajor else "packed at load (moe_pack_weights)",
+                   "weights": ("4-bit microscaling FP4 (e2m1 + e8m0 per 32), packed at load" if mx else
+                               "row-major" if args.rowmajor else "packed at load (moe_pack_weights)"),
                    "units": int(g.ctx.cursor.n_units)},
         "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
         "stages_ms": stages,

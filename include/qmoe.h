@@ -78,6 +78,9 @@ typedef struct {
     const void *W3; /* [device] up_proj        [E,F,H] (H contiguous)                           */
     const void *W2; /* [device] down_proj      [E,H,F] (F contiguous)                           */
     int32_t layout; /* MOE_W_ROWMAJOR: the shapes above.  MOE_W_PACKED: written by moe_pack_weights */
+    const void *S1; /* [device] 4-bit layouts only: block scales of W1, W3, W2 (else NULL)          */
+    const void *S3;
+    const void *S2;
 } moe_weights;
 
 /* Weight layouts.  MOE_W_PACKED (bf16 only) stores every expert matrix M [R,K] (R % 32 == 0,
@@ -86,7 +89,22 @@ typedef struct {
  *     element (r, k)  ->  (((r/32) * (K/16) + k/16) * 64 + (r%32) + 32*((k%16)/8)) * 8 + k%8
  * per expert, experts back to back (same total size as row-major); Wg is stored transposed and
  * padded: [ceil16(E), H], rows >= E zero. */
-enum { MOE_W_ROWMAJOR = 0, MOE_W_PACKED = 1 };
+enum { MOE_W_ROWMAJOR = 0, MOE_W_PACKED = 1, MOE_W_MXFP4_ROWMAJOR = 2, MOE_W_MXFP4 = 3 };
+
+/* 4-bit expert weights (the paper evaluates its model with 4-bit quantised weights and 16-bit
+ * activations, Sec. 4 "Models and Dataset", without naming a format; this library takes the open
+ * microscaling FP4 format): an element is a 4-bit float e2m1 (sign, 2 exponent bits, 1 mantissa bit:
+ * +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}), every 32 consecutive elements along K share one scale byte e8m0
+ * (2^(byte-127)); value = element * scale, always exactly a bf16.  cfg.dtype stays MOE_BF16 (x, y and
+ * the activation are bf16, Wg is bf16 [H,E]); only W1, W3, W2 are 4-bit.
+ * MOE_W_MXFP4_ROWMAJOR (input of moe_pack_weights only): W1/W3 [E,F,H/2] and W2 [E,H,F/2] bytes, the
+ * element with even k in the low nibble; S1/S3 [E,F,H/32], S2 [E,H,F/32] scale bytes.
+ * MOE_W_MXFP4 (what moe_route / moe_expert_run accept): per expert and matrix M [R,K] (R % 32 == 0,
+ * K % 64 == 0) the codes as 1 KiB blocks, block (r/32, k/64) at ((r/32)*(K/64) + k/64) * 1024 bytes,
+ * inside it lane l = r%32 + 32*((k%16)/8) owns 16 bytes: 4 little-endian words, word (k%64)/16 holds
+ * the 8 elements k%8 = 0..7 (element j in bits 4j..4j+3); the scales as 64-byte blocks in the same
+ * block order, row r%32 owning 2 bytes: the scales of k%64 < 32 and of k%64 >= 32.  Same sizes as
+ * the row-major form.  Wg as in MOE_W_PACKED. */
 
 /* Where a layer-batch stands in its work-unit list.  A plain value: keeping a copy of it (and the
  * context's workspace) is all a preempted batch needs in order to resume. */
@@ -133,10 +151,11 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
 int32_t moe_destroy(moe_ctx *ctx);
 
 /* One-time re-layout of the weights at model load (outside any timed region).  src: row-major
- * weights (layout MOE_W_ROWMAJOR).  dst: caller-allocated [device] buffers, W1/W3/W2 of the same
- * sizes as the sources, Wg of ceil16(E)*H elements; on success dst->layout is set to MOE_W_PACKED
- * and dst can be passed wherever weights are expected.  Results are bit-identical for both
- * layouts.  bf16 only (MOE_E_ARG for MOE_F32).  Enqueues on `stream` and returns. */
+ * weights, layout MOE_W_ROWMAJOR (bf16) or MOE_W_MXFP4_ROWMAJOR (4-bit codes and scales).  dst:
+ * caller-allocated [device] buffers, W1/W3/W2 (and S1/S3/S2 for the 4-bit form) of the same sizes as
+ * the sources, Wg of ceil16(E)*H bf16 elements; on success dst->layout is set to MOE_W_PACKED or
+ * MOE_W_MXFP4.  The expert kernels produce bit-identical results for the row-major and the packed
+ * bf16 layout.  cfg->dtype must be MOE_BF16 (MOE_E_ARG otherwise).  Enqueues on `stream` and returns. */
 int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weights *dst, void *stream);
 
 /* Router (Sec. 2.1: "a router that assigns each token to the most relevant experts"; Sec. 2.2).

@@ -5,7 +5,9 @@ from .oracle import (  # noqa: F401
     OracleLayer,
     build,
     combine,
+    dequant_mxfp4,
     expert_rows,
+    mxfp4_weights_as_bf16,
     gate_logits,
     queues,
     route,

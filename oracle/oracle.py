@@ -189,6 +189,38 @@ def combine(O, done, inv, wt, tokens, H: int):
     return y, comp.astype(bool)
 
 
+# e2m1 (sign, 2 exponent bits, 1 mantissa bit; exponent bias 1, code 0/1 subnormal): the 4-bit
+# element of the open microscaling FP4 format this build reads the paper's "4-bit quantization" as
+# (section "Evaluation", models and dataset).  Indexed by the low three bits; bit 3 is the sign.
+_E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
+
+
+def dequant_mxfp4(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """4-bit weights -> fp64 values.  codes uint8 [..., K/2] (element with even k in the low nibble),
+    scales uint8 [..., K/32] (e8m0: 2^(byte-127), one per 32 consecutive elements).  Returns [..., K]."""
+    codes, scales = _c(codes, np.uint8), _c(scales, np.uint8)
+    K = codes.shape[-1] * 2
+    assert scales.shape[-1] * 32 == K and codes.shape[:-1] == scales.shape[:-1]
+    nib = np.empty(codes.shape[:-1] + (K,), dtype=np.uint8)
+    nib[..., 0::2] = codes & 0x0F
+    nib[..., 1::2] = codes >> 4
+    val = _E2M1[nib & 7] * np.where(nib & 8, -1.0, 1.0)
+    scale = np.ldexp(1.0, scales.astype(np.int64) - 127)
+    return val * np.repeat(scale, 32, axis=-1)
+
+
+def mxfp4_weights_as_bf16(w: dict) -> dict:
+    """The weights dict of the layer functions (bf16 bit patterns) for 4-bit weights: every
+    element * scale is exactly representable in bf16, which is asserted."""
+    out = {"Wg": w["Wg"]}
+    for n in ("W1", "W3", "W2"):
+        v = dequant_mxfp4(w[n + "q"], w[n + "s"]).astype(np.float32)
+        bits = v.view(np.uint32)
+        assert not (bits & 0xFFFF).any()
+        out[n] = (bits >> 16).astype(np.uint16)
+    return out
+
+
 class OracleLayer:
     """One layer-batch walked unit by unit: the state a preempted job keeps (expert
     assignment, routing weights, queue order, finished expert rows) and nothing else."""

@@ -16,7 +16,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_OK, MOE_DONE = 0, 1
 MOE_E_ARG, MOE_E_STATE, MOE_E_INCOMPLETE, MOE_E_WORKSPACE, MOE_E_HIP = -1, -2, -3, -4, -5
 MOE_CLASS_LS, MOE_CLASS_BE, MOE_CLASS_ALL = 1, 2, 3
-MOE_W_ROWMAJOR, MOE_W_PACKED = 0, 1
+MOE_W_ROWMAJOR, MOE_W_PACKED, MOE_W_MXFP4_ROWMAJOR, MOE_W_MXFP4 = 0, 1, 2, 3
 UINT32_MAX = 0xFFFFFFFF
 
 GET = {"logits": 0, "topk_idx": 1, "topk_w": 2, "counts": 3, "offsets": 4, "perm": 5, "inv": 6,
@@ -31,7 +31,7 @@ class MoeConfig(C.Structure):
 
 class MoeWeights(C.Structure):
     _fields_ = [("Wg", C.c_void_p), ("W1", C.c_void_p), ("W3", C.c_void_p), ("W2", C.c_void_p),
-                ("layout", C.c_int32)]
+                ("layout", C.c_int32), ("S1", C.c_void_p), ("S3", C.c_void_p), ("S2", C.c_void_p)]
 
 
 class MoeCursor(C.Structure):
@@ -186,8 +186,8 @@ class Context:
             pass
 
     @staticmethod
-    def weights(Wg, W1, W3, W2, layout: int = MOE_W_ROWMAJOR) -> MoeWeights:
-        return MoeWeights(_ptr(Wg), _ptr(W1), _ptr(W3), _ptr(W2), layout)
+    def weights(Wg, W1, W3, W2, layout: int = MOE_W_ROWMAJOR, S1=None, S3=None, S2=None) -> MoeWeights:
+        return MoeWeights(_ptr(Wg), _ptr(W1), _ptr(W3), _ptr(W2), layout, _ptr(S1), _ptr(S3), _ptr(S2))
 
     def route(self, x, w: MoeWeights, bias=None, n_tokens=None):
         n = x.shape[0] if n_tokens is None else n_tokens

@@ -49,7 +49,42 @@ __global__ __launch_bounds__(256) void pack_weights_bf16(const uint4 *__restrict
     dst[i] = src[(e * R + r) * (K / 8) + k / 8];
 }
 
+// Re-layout of 4-bit weights: one thread per 16-byte piece of the destination (expert, row tile,
+// iteration, lane); lanes of the lower k-half also write their row's two scale bytes.
+__global__ __launch_bounds__(256) void pack_weights_mxfp4(const uint8_t *__restrict__ codes, const uint8_t *__restrict__ scales,
+                                                          uint4 *__restrict__ dcodes, uint16_t *__restrict__ dscales,
+                                                          long pieces, int R, int K) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= pieces) return;
+    const int lane = (int)(i & 63);
+    const long blk = i >> 6;                                // (e * R/32 + nt) * K/64 + it
+    const int kb = K >> 6;
+    const int it = (int)(blk % kb);
+    const long row_tile = blk / kb;                         // e * R/32 + nt
+    const long row = row_tile * 32 + (lane & 31);           // e * R + r
+    const int lh = lane >> 5;
+    const uint8_t *src = codes + (row * K + it * 64 + lh * 8) / 2;
+    uint4 v;
+    v.x = *reinterpret_cast<const uint32_t *>(src);
+    v.y = *reinterpret_cast<const uint32_t *>(src + 8);
+    v.z = *reinterpret_cast<const uint32_t *>(src + 16);
+    v.w = *reinterpret_cast<const uint32_t *>(src + 24);
+    dcodes[i] = v;
+    if (lh == 0) {
+        const uint8_t *sp = scales + row * (K >> 5) + it * 2;
+        dscales[blk * 32 + lane] = (uint16_t)(sp[0] | (sp[1] << 8));
+    }
+}
+
 }  // namespace
+
+hipError_t launch_pack_mxfp4(const void *codes, const void *scales, void *dcodes, void *dscales, int E, int R, int K,
+                             hipStream_t s) {
+    const long pieces = (long)E * (R / 32) * (K / 64) * 64;
+    hipLaunchKernelGGL(pack_weights_mxfp4, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const uint8_t *)codes,
+                       (const uint8_t *)scales, (uint4 *)dcodes, (uint16_t *)dscales, pieces, R, K);
+    return hipGetLastError();
+}
 
 hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStream_t s) {
     const long pieces = (long)E * R * K / 8;
@@ -96,7 +131,8 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     b.k = gu_in;
     b.k.col_tiles = (a.F + 127) / 128;
     auto launch = [&](bool gateup) {
-        if (a.packed) bf16k::launch_expert_kernels<bf16k::WF_PACKED>(gateup, tiles, stream, b, s);
+        if (a.wfmt == bf16k::WF_MXFP4) bf16k::launch_expert_kernels<bf16k::WF_MXFP4>(gateup, tiles, stream, b, s);
+        else if (a.wfmt == bf16k::WF_PACKED) bf16k::launch_expert_kernels<bf16k::WF_PACKED>(gateup, tiles, stream, b, s);
         else bf16k::launch_expert_kernels<bf16k::WF_ROWMAJOR>(gateup, tiles, stream, b, s);
     };
     { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch(true); }

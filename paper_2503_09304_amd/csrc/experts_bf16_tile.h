@@ -43,14 +43,17 @@
 namespace qmoe {
 namespace bf16k {
 
-// Weight formats of the expert matrices.
-enum { WF_ROWMAJOR = 0, WF_PACKED = 1 };
+// Weight formats of the expert matrices: bf16 row-major, bf16 in MFMA-ordered 1 KiB blocks, and
+// 4-bit microscaling floats (e2m1 elements, one power-of-two e8m0 scale per 32 elements along K) in
+// MFMA-ordered blocks, turned into bf16 operands in registers (exactly: every such value is a bf16).
+enum { WF_ROWMAJOR = 0, WF_PACKED = 1, WF_MXFP4 = 2 };
 
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
 
@@ -97,11 +100,33 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     // ---- weight rows of this lane (B operand) ----
     // Row-major: lane = (row l%32, k-half l/32), 16 elements per k-step, 64 per iteration.
     // Packed: the wave's 1 KiB block of k-step s of row tile nt starts at (nt*(K/16)+s)*512.
+    // MXFP4: per (row tile, iteration) one KiB of codes (lane l: 16 bytes = the 8 elements of each
+    // of the 4 k-steps) and 64 bytes of scales (row l%32: the two e8m0 bytes of the iteration's two
+    // 32-element blocks).
     constexpr bool PACKED = WF == WF_PACKED;
+    constexpr bool MX = WF == WF_MXFP4;
     constexpr int BKS = PACKED ? 512 : 16;   // elements between k-steps
     constexpr int BIT = PACKED ? 2048 : 64;  // elements between iterations
     const uint16_t *bptr[2];
-    {
+    const char *cptr[2];                     // MXFP4 codes
+    const char *sptr[2];                     // MXFP4 scales
+    if constexpr (MX) {
+        const int ntiles = p.ncols >> 5;
+        const int nt0 = min(col_base >> 5, ntiles - 1);
+        const int nt1 = GATEUP ? nt0 : min((col_base >> 5) + 1, ntiles - 1);
+        const long kblocks = p.K >> 6;                              // iterations per row tile
+        const char *c0 = (const char *)p.b0 + (long)un.expert * (p.b_estride >> 1);
+        const char *c1 = GATEUP ? (const char *)p.b1 + (long)un.expert * (p.b_estride >> 1) : c0;
+        const char *s0 = (const char *)p.s0 + (long)un.expert * (p.b_estride >> 5);
+        const char *s1 = GATEUP ? (const char *)p.s1 + (long)un.expert * (p.b_estride >> 5) : s0;
+        const long it0 = (long)kq * (Kg >> 6);
+        cptr[0] = c0 + ((nt0 * kblocks + it0) * 64 + l) * 16;
+        cptr[1] = c1 + ((nt1 * kblocks + it0) * 64 + l) * 16;
+        sptr[0] = s0 + ((nt0 * kblocks + it0) * 32 + lr) * 2;
+        sptr[1] = s1 + ((nt1 * kblocks + it0) * 32 + lr) * 2;
+        bptr[0] = bptr[1] = nullptr;
+    } else {
+        cptr[0] = cptr[1] = sptr[0] = sptr[1] = nullptr;
         const uint16_t *b0 = (const uint16_t *)p.b0 + (long)un.expert * p.b_estride;
         const uint16_t *b1 = GATEUP ? (const uint16_t *)p.b1 + (long)un.expert * p.b_estride : b0;
         if (PACKED) {
@@ -146,7 +171,9 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     constexpr int DA = T >= 8 ? 1 : D;   // token pieces: same distance, or 1 where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
-    bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]
+    bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]; MXFP4: set 0 only, the operands of the current iteration
+    u32x4 c_reg[NB * 2];   // MXFP4: codes [set][n-tile]
+    unsigned short s_reg[NB * 2];   // MXFP4: the two scale bytes [set][n-tile]
 
     auto load_a = [&](int it, auto setc) {
         constexpr int S = decltype(setc)::value;
@@ -167,6 +194,17 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     auto load_b = [&](int it, auto setc) {
         constexpr int S = decltype(setc)::value;
         const int itc = min(it, iters - 1);
+        if constexpr (MX) {
+            static_for<2>([&](auto nc) {
+                constexpr int n = decltype(nc)::value;
+                const u32x4 *qc = reinterpret_cast<const u32x4 *>(cptr[n] + (long)itc * 1024);
+                const unsigned short *qs = reinterpret_cast<const unsigned short *>(sptr[n] + (long)itc * 64);
+                if constexpr (STREAM) c_reg[S * 2 + n] = __builtin_nontemporal_load(qc);
+                else c_reg[S * 2 + n] = *qc;
+                s_reg[S * 2 + n] = *qs;
+            });
+            return;
+        }
         static_for<4>([&](auto kc) {
             constexpr int ks = decltype(kc)::value;
             const bf16x8 *q0 = reinterpret_cast<const bf16x8 *>(bptr[0] + (long)itc * BIT + ks * BKS);
@@ -193,8 +231,33 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
             af[(hs & 1) * HT + decltype(tc)::value] = *reinterpret_cast<const bf16x8 *>(lds + stage * STAGE + (r * 8 + slot) * 16);
         });
     };
-    auto mfma_tile = [&](int stage, auto setc) {
+    // MXFP4: codes and scales of ring set S -> bf16 operands (v_cvt_scalef32_pk_bf16_fp4: two e2m1
+    // nibbles of one byte times a float scale, exact for a power-of-two scale).
+    auto dequant_b = [&](auto setc) {
         constexpr int S = decltype(setc)::value;
+        static_for<2>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            const unsigned sc = s_reg[S * 2 + n];
+            const float f0 = __builtin_bit_cast(float, (sc & 0xffu) << 23);
+            const float f1 = __builtin_bit_cast(float, (sc >> 8) << 23);
+            static_for<4>([&](auto kc) {
+                constexpr int ks = decltype(kc)::value;
+                const unsigned wv = c_reg[S * 2 + n][ks];
+                const float f = ks < 2 ? f0 : f1;
+                const bf16x2 e0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(wv, f, 0);
+                const bf16x2 e1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(wv, f, 1);
+                const bf16x2 e2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(wv, f, 2);
+                const bf16x2 e3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(wv, f, 3);
+                bf16x8 v;
+                v[0] = e0[0]; v[1] = e0[1]; v[2] = e1[0]; v[3] = e1[1];
+                v[4] = e2[0]; v[5] = e2[1]; v[6] = e3[0]; v[7] = e3[1];
+                b_reg[ks * 2 + n] = v;
+            });
+        });
+    };
+    auto mfma_tile = [&](int stage, auto setc) {
+        constexpr int S = MX ? 0 : decltype(setc)::value;
+        if constexpr (MX) dequant_b(setc);
         read_af(stage, std::integral_constant<int, 0>{});
         static_for<STEPS>([&](auto hsc) {
             constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;
@@ -399,6 +462,7 @@ void launch_expert_kernels(bool gateup, int tiles, bool stream, const BArgs &b, 
 
 extern template void launch_expert_kernels<WF_ROWMAJOR>(bool, int, bool, const BArgs &, hipStream_t);
 extern template void launch_expert_kernels<WF_PACKED>(bool, int, bool, const BArgs &, hipStream_t);
+extern template void launch_expert_kernels<WF_MXFP4>(bool, int, bool, const BArgs &, hipStream_t);
 
 }  // namespace bf16k
 }  // namespace qmoe

@@ -11,6 +11,7 @@ struct KArgs {
     const void *a_src;      // x [N,H] (gate-up) or act [A,F] (down)
     const int32_t *perm;    // gate-up: sorted row -> assignment id; down: nullptr
     const void *b0, *b1;    // gate-up: W1, W3; down: W2, unused
+    const void *s0, *s1;    // 4-bit weights: the block scales of b0, b1 (else nullptr)
     void *dst;              // gate-up: act; down: out (fp32)
     const moe_unit *units;
     long b_estride;         // elements per expert in b0/b1

@@ -171,16 +171,28 @@ int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weig
     if (cfg->dtype != MOE_BF16) return fail(MOE_E_ARG, "moe_pack_weights: bf16 only");
     if (!src || !dst || !src->Wg || !src->W1 || !src->W3 || !src->W2 || !dst->Wg || !dst->W1 || !dst->W3 || !dst->W2)
         return fail(MOE_E_ARG, "moe_pack_weights: null pointer");
-    if (src->layout != MOE_W_ROWMAJOR) return fail(MOE_E_ARG, "moe_pack_weights: source must be row-major");
+    if (src->layout != MOE_W_ROWMAJOR && src->layout != MOE_W_MXFP4_ROWMAJOR)
+        return fail(MOE_E_ARG, "moe_pack_weights: source must be row-major (bf16 or 4-bit)");
     if (src->W1 == dst->W1 || src->W3 == dst->W3 || src->W2 == dst->W2 || src->Wg == dst->Wg)
         return fail(MOE_E_ARG, "moe_pack_weights: cannot pack in place");
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = qmoe::launch_pack(src->W1, const_cast<void *>(dst->W1), cfg->E, cfg->F, cfg->H, s);
-    if (e == hipSuccess) e = qmoe::launch_pack(src->W3, const_cast<void *>(dst->W3), cfg->E, cfg->F, cfg->H, s);
-    if (e == hipSuccess) e = qmoe::launch_pack(src->W2, const_cast<void *>(dst->W2), cfg->E, cfg->H, cfg->F, s);
+    hipError_t e;
+    if (src->layout == MOE_W_MXFP4_ROWMAJOR) {
+        if (!src->S1 || !src->S3 || !src->S2 || !dst->S1 || !dst->S3 || !dst->S2)
+            return fail(MOE_E_ARG, "moe_pack_weights: 4-bit weights need the scale pointers S1, S3, S2");
+        if (src->S1 == dst->S1 || src->S3 == dst->S3 || src->S2 == dst->S2)
+            return fail(MOE_E_ARG, "moe_pack_weights: cannot pack in place");
+        e = qmoe::launch_pack_mxfp4(src->W1, src->S1, const_cast<void *>(dst->W1), const_cast<void *>(dst->S1), cfg->E, cfg->F, cfg->H, s);
+        if (e == hipSuccess) e = qmoe::launch_pack_mxfp4(src->W3, src->S3, const_cast<void *>(dst->W3), const_cast<void *>(dst->S3), cfg->E, cfg->F, cfg->H, s);
+        if (e == hipSuccess) e = qmoe::launch_pack_mxfp4(src->W2, src->S2, const_cast<void *>(dst->W2), const_cast<void *>(dst->S2), cfg->E, cfg->H, cfg->F, s);
+    } else {
+        e = qmoe::launch_pack(src->W1, const_cast<void *>(dst->W1), cfg->E, cfg->F, cfg->H, s);
+        if (e == hipSuccess) e = qmoe::launch_pack(src->W3, const_cast<void *>(dst->W3), cfg->E, cfg->F, cfg->H, s);
+        if (e == hipSuccess) e = qmoe::launch_pack(src->W2, const_cast<void *>(dst->W2), cfg->E, cfg->H, cfg->F, s);
+    }
     if (e == hipSuccess) e = qmoe::launch_pack_gate(src->Wg, const_cast<void *>(dst->Wg), cfg->H, cfg->E, s);
     if (e != hipSuccess) return hip_fail(e, "moe_pack_weights: launch");
-    dst->layout = MOE_W_PACKED;
+    dst->layout = src->layout == MOE_W_MXFP4_ROWMAJOR ? MOE_W_MXFP4 : MOE_W_PACKED;
     return MOE_OK;
 }
 
@@ -226,8 +238,10 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens)
         return fail(MOE_E_ARG, "moe_route: n_tokens %d outside 0..%d", n_tokens, ctx->cfg.max_tokens);
     if (!w || !w->Wg || !w->W1 || !w->W3 || !w->W2) return fail(MOE_E_ARG, "moe_route: null weight pointer");
-    if (w->layout != MOE_W_ROWMAJOR && w->layout != MOE_W_PACKED) return fail(MOE_E_ARG, "moe_route: unknown weight layout %d", w->layout);
-    if (w->layout == MOE_W_PACKED && ctx->cfg.dtype != MOE_BF16) return fail(MOE_E_ARG, "moe_route: packed weights are bf16 only");
+    if (w->layout != MOE_W_ROWMAJOR && w->layout != MOE_W_PACKED && w->layout != MOE_W_MXFP4)
+        return fail(MOE_E_ARG, "moe_route: weight layout %d is not one the kernels read (row-major 4-bit weights go through moe_pack_weights)", w->layout);
+    if (w->layout != MOE_W_ROWMAJOR && ctx->cfg.dtype != MOE_BF16) return fail(MOE_E_ARG, "moe_route: packed weights are bf16 only");
+    if (w->layout == MOE_W_MXFP4 && (!w->S1 || !w->S3 || !w->S2)) return fail(MOE_E_ARG, "moe_route: 4-bit weights need the scale pointers S1, S3, S2");
     if (n_tokens > 0 && !x) return fail(MOE_E_ARG, "moe_route: null x");
     if (!ctx->pinned) {
         hipError_t e = hipHostMalloc((void **)&ctx->pinned, (2 * (size_t)ctx->cfg.E + 1) * sizeof(int32_t), hipHostMallocDefault);
@@ -241,7 +255,7 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
         a.topk_idx = at<int32_t>(ctx, ctx->lay.topk_idx);
         a.topk_w = at<float>(ctx, ctx->lay.topk_w);
         a.N = n_tokens; a.H = ctx->cfg.H; a.E = ctx->cfg.E; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
-        a.packed = w->layout == MOE_W_PACKED;
+        a.packed = w->layout != MOE_W_ROWMAJOR;      // Wg transposed and padded
         hipError_t e = qmoe::launch_route(a, (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "moe_route: launch");
     }
@@ -327,7 +341,8 @@ static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, 
     a.out = at<float>(ctx, ctx->lay.out);
     a.H = ctx->cfg.H; a.F = ctx->cfg.F; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype;
     a.prof = ctx->prof_on ? &ctx->prof : nullptr;
-    a.packed = w->layout == MOE_W_PACKED;
+    a.wfmt = w->layout == MOE_W_MXFP4 ? 2 : (w->layout == MOE_W_PACKED ? 1 : 0);
+    a.S1 = w->S1; a.S3 = w->S3; a.S2 = w->S2;
     a.ksplit = ctx->lay.has_partial ? 4 : 1;
     a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
     a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
@@ -402,7 +417,8 @@ static int32_t check_run_args(moe_ctx *ctx, const void *x, const moe_weights *w,
     if (!ctx) return fail(MOE_E_ARG, "%s: null context", who);
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "%s: call moe_permute first", who);
     if (!w || (ctx->N > 0 && !x)) return fail(MOE_E_ARG, "%s: null x or weights", who);
-    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout)
+    if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout ||
+        w->S1 != ctx->w.S1 || w->S3 != ctx->w.S3 || w->S2 != ctx->w.S2)
         return fail(MOE_E_ARG, "%s: x and weights must be the tensors given to moe_route", who);
     return MOE_OK;
 }

@@ -78,7 +78,8 @@ struct ExpertArgs {
     uint32_t u0, nu;        // units [u0, u0+nu)
     int max_rows;           // largest rows among the segments (or units) of the launch
     Profiler *prof;             // nullptr unless timing is on
-    bool packed;                // expert weights in the MFMA-ordered 1 KiB-block layout
+    int wfmt;                   // expert weights: 0 bf16 row-major, 1 bf16 in MFMA-ordered blocks, 2 4-bit blocks
+    const void *S1, *S3, *S2;   // 4-bit weights: block scales
     const Seg *segs;            // host array [nseg] (nseg <= kMaxSegs), or nullptr: use the unit list
     int nseg;
     int ksplit;                 // 1 or 4 (down projection; fixed per context)
@@ -89,6 +90,9 @@ hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
 
 // Re-layout of one [E][R][K] bf16 tensor into the packed block order (see MOE_W_PACKED).
 hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStream_t s);
+// Re-layout of 4-bit codes [E][R][K/2] and scales [E][R][K/32] into the MOE_W_MXFP4 block order.
+hipError_t launch_pack_mxfp4(const void *codes, const void *scales, void *dcodes, void *dscales, int E, int R, int K,
+                             hipStream_t s);
 hipError_t launch_pack_gate(const void *Wg, void *WgT, int H, int E, hipStream_t s);
 
 struct CombineArgs {

@@ -50,6 +50,36 @@ class DevWeights:
         return self._packed
 
 
+class DevWeightsMX:
+    """4-bit expert weights on the device: row-major codes and scales as generated, and .packed(),
+    the block order the kernels read.  Same attributes as DevWeights where the layer needs them."""
+
+    def __init__(self, w):
+        self.Wg = to_dev(w["Wg"])
+        for n in ("W1", "W3", "W2"):
+            setattr(self, n, torch.from_numpy(w[n + "q"]).to(DEV))
+            setattr(self, "S" + n[1], torch.from_numpy(w[n + "s"]).to(DEV))
+        self.struct = q.Context.weights(self.Wg, self.W1, self.W3, self.W2, q.MOE_W_MXFP4_ROWMAJOR, self.S1, self.S3, self.S2)
+        self._packed = None
+
+    def packed(self) -> "DevWeightsMX":
+        if self._packed is None:
+            H, E = self.Wg.shape
+            F = self.W1.shape[1]
+            p = object.__new__(DevWeightsMX)
+            p.Wg = torch.empty(((E + 15) // 16 * 16, H), dtype=self.Wg.dtype, device=DEV)
+            for n in ("W1", "W3", "W2", "S1", "S3", "S2"):
+                setattr(p, n, torch.empty_like(getattr(self, n)))
+            p.struct = q.Context.weights(p.Wg, p.W1, p.W3, p.W2, q.MOE_W_MXFP4_ROWMAJOR, p.S1, p.S3, p.S2)
+            cfg = q.MoeConfig(E, 1, H, F, q.MOE_BF16, 1, 0)
+            q.moe_pack_weights(cfg, self.struct, p.struct)
+            torch.cuda.synchronize()
+            assert p.struct.layout == q.MOE_W_MXFP4
+            p._packed = p
+            self._packed = p
+        return self._packed
+
+
 class GpuLayer:
     """One layer-batch on the device."""
 

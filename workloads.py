@@ -183,6 +183,22 @@ def make_weights(cfg: LayerConfig, threads: int = 8) -> Dict[str, np.ndarray]:
     return out
 
 
+def make_weights_mxfp4(cfg: LayerConfig) -> Dict[str, np.ndarray]:
+    """Seeded synthetic 4-bit expert weights in the microscaling FP4 storage form: for W1/W3 [E,F,H]
+    and W2 [E,H,F] one byte per two elements along K (even k in the low nibble), codes uniform over
+    the 16 e2m1 patterns, and one e8m0 scale byte per 32 elements drawn from 2^-8, 2^-7, 2^-6 (the
+    values then have a standard deviation of about 0.02-0.03, like the bf16 recipe).  Wg stays bf16.
+    Only random draws here: what the codes mean is the business of whoever consumes them."""
+    ws = cfg.weight_seed if cfg.weight_seed is not None else cfg.seed
+    out = {"Wg": _normal(ws, "wg", 0, (cfg.H, cfg.E), 0.02, "bf16")}
+    for name, tag, (R, K) in (("W1", "w1", (cfg.F, cfg.H)), ("W3", "w3", (cfg.F, cfg.H)), ("W2", "w2", (cfg.H, cfg.F))):
+        assert K % 32 == 0
+        rng = _rng(ws, tag, 4000)
+        out[name + "q"] = rng.integers(0, 256, size=(cfg.E, R, K // 2), dtype=np.uint8)
+        out[name + "s"] = rng.integers(119, 122, size=(cfg.E, R, K // 32), dtype=np.uint8)
+    return out
+
+
 @dataclass
 class LayerInputs:
     cfg: LayerConfig
