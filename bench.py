@@ -28,7 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2025716848, "cfg4": 1911724565, "cfg3_be": 5219285068, "cfg5": 3336967616}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2027035667, "cfg4": 1910454088, "cfg3_be": 5302723814, "cfg5": 3308191981,
+                          "cfg4_mxfp4": 514429492, "cfg3_be_mxfp4": 1898109125}
 
 
 def log(*a):
