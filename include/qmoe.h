@@ -229,13 +229,15 @@ int32_t moe_units(moe_ctx *ctx, moe_unit *out, uint32_t cap, uint32_t *n_units);
 int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_unit *out,
                        uint32_t cap, uint32_t *n_units);
 
-/* Per-kernel timing for benchmarks.  moe_profile(ctx, 1) makes moe_expert_run bracket each of its
- * kernel launches with a pair of HIP events on the caller's stream (events are created on demand
- * and kept by the context); moe_profile(ctx, 0) turns that off.  moe_profile_read waits for the
- * recorded events, adds up elapsed milliseconds and launch counts per kernel kind since the last
- * read into ms / launches ([host], MOE_PROF_KINDS entries each) and forgets them. */
-enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2, MOE_PROF_KINDS = 3 };
-int32_t moe_profile(moe_ctx *ctx, int32_t enable);
+/* Per-kernel timing for benchmarks.  moe_profile(ctx, kinds) makes moe_expert_run bracket the kernel
+ * launches of the selected kinds with a pair of HIP events on the caller's stream (events are
+ * created on demand and kept by the context); kinds is a bit mask, bit MOE_PROF_x per kind,
+ * MOE_PROF_ALL for every kind, 0 turns the bracketing off.  Each bracketed launch costs a few
+ * microseconds of stream time.  moe_profile_read waits for the recorded events, adds up elapsed
+ * milliseconds and launch counts per kernel kind since the last read into ms / launches ([host],
+ * MOE_PROF_KINDS entries each) and forgets them. */
+enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2, MOE_PROF_KINDS = 3, MOE_PROF_ALL = 7 };
+int32_t moe_profile(moe_ctx *ctx, int32_t kinds);
 int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */

@@ -222,8 +222,16 @@ class Context:
             raise TypeError("complete must be a uint8 tensor")
         return _check(lib().moe_combine_complete(self.h, _ptr(y), _ptr(complete), _stream()))
 
-    def profile(self, enable: bool) -> None:
-        _check(lib().moe_profile(self.h, 1 if enable else 0))
+    def profile(self, kinds) -> None:
+        """Bracket the expert kernels of the given kinds with events: True = all, False = none, or an
+        iterable of names out of gate_up, down, down_reduce."""
+        if kinds is True:
+            mask = 7
+        elif not kinds:
+            mask = 0
+        else:
+            mask = sum(1 << ("gate_up", "down", "down_reduce").index(k) for k in kinds)
+        _check(lib().moe_profile(self.h, mask))
 
     def profile_read(self):
         """{kind: (total ms, launches)} of the expert kernels since the last read."""

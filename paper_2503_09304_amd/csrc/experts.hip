@@ -17,11 +17,16 @@ hipEvent_t Profiler::get() {
     return e;
 }
 void Profiler::begin(int kind, hipStream_t s) {
+    live = (kinds >> kind) & 1;
+    if (!live) return;
     Span sp{kind, get(), get()};
     (void)hipEventRecord(sp.a, s);
     spans.push_back(sp);
 }
-void Profiler::end(hipStream_t s) { (void)hipEventRecord(spans.back().b, s); }
+void Profiler::end(hipStream_t s) {
+    if (live) (void)hipEventRecord(spans.back().b, s);
+    live = false;
+}
 
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s) {
     if (a.nu == 0 && a.nseg == 0) return hipSuccess;

@@ -547,9 +547,11 @@ int32_t moe_get(moe_ctx *ctx, int32_t what, const void **dev_ptr, size_t *bytes)
     return MOE_OK;
 }
 
-int32_t moe_profile(moe_ctx *ctx, int32_t enable) {
+int32_t moe_profile(moe_ctx *ctx, int32_t kinds) {
     if (!ctx) return fail(MOE_E_ARG, "moe_profile: null context");
-    ctx->prof_on = enable != 0;
+    if (kinds < 0 || kinds > MOE_PROF_ALL) return fail(MOE_E_ARG, "moe_profile: kinds must be a mask of MOE_PROF_* bits (0..%d)", MOE_PROF_ALL);
+    ctx->prof_on = kinds != 0;
+    ctx->prof.kinds = kinds;
     return MOE_OK;
 }
 

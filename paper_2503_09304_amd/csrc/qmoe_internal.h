@@ -62,6 +62,8 @@ struct Profiler {
     struct Span { int kind; hipEvent_t a, b; };
     std::vector<Span> spans;        // recorded since the last read
     std::vector<hipEvent_t> pool;   // events free for reuse
+    int kinds = 0;                  // bit mask of the kernel kinds to bracket
+    bool live = false;              // the span opened by the last begin() is being recorded
     hipEvent_t get();
     void begin(int kind, hipStream_t s);
     void end(hipStream_t s);
