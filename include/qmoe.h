@@ -173,7 +173,10 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
  * work-unit list: phase LS then phase BE; inside a phase experts ascending; inside one expert's
  * sub-queue consecutive chunks of chunk_rows rows, the last one short; empty sub-queues give no
  * unit.  Waits for the counts (the engine's report to the scheduler after the router stage,
- * Sec. 3.2) and returns the cursor {0, n_units} in *cursor ([host]). */
+ * Sec. 3.2): the kernel stores them into pinned host memory as soon as it knows them and the call
+ * polls for that, so it returns while the rest of the permutation may still be running; whatever is
+ * enqueued on the stream afterwards is ordered behind it.  Returns the cursor {0, n_units} in
+ * *cursor ([host]). */
 int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void *stream);
 
 /* Expert work, resumable (Sec. 3.1 "Top-k expert selection"; Introduction, contribution 3).

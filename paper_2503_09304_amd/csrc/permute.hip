@@ -78,10 +78,22 @@ __device__ int block_excl_scan(int32_t *v, int32_t *tmp, int n) {
     return total;
 }
 
+// The engine's report to the scheduler after the router stage (Sec. 3.2): the queue lengths and the
+// unit count go straight into host memory as soon as they are known, before the ranking work, and the
+// sequence word is stored last, after a system-scope fence, so a host that sees the sequence number
+// sees the report.  Called by every thread of the one workgroup that knows the totals.
+__device__ __forceinline__ void report_to_host(int32_t *__restrict__ report, int32_t seq, const int32_t *tot, int nb, int nu) {
+    for (int b = threadIdx.x; b < nb; b += blockDim.x) report[b] = tot[b];
+    if (threadIdx.x == 0) report[nb] = nu;
+    __threadfence_system();
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_store(report + nb + 1, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ __launch_bounds__(1024) void perm_scan(int32_t *__restrict__ blockcnt, int nblocks, int E, int C,
                                                   int32_t *__restrict__ cnt, int32_t *__restrict__ off,
                                                   moe_unit *__restrict__ units, int32_t *__restrict__ n_units,
-                                                  int max_units) {
+                                                  int max_units, int32_t *__restrict__ report, int32_t seq) {
     __shared__ int32_t tot[2 * kMaxExperts];
     __shared__ int32_t boff[2 * kMaxExperts];
     __shared__ int32_t ustart[2 * kMaxExperts];
@@ -112,6 +124,7 @@ __global__ __launch_bounds__(1024) void perm_scan(int32_t *__restrict__ blockcnt
     __syncthreads();
     const int nu = block_excl_scan(ustart, tmp, nb);
     if (tid == 0) *n_units = nu;
+    report_to_host(report, seq, tot, nb, nu);
     for (int q = tid; q < nb; q += blockDim.x) {
         const int cl = q / E, e = q - cl * E;
         const int len = tot[2 * e + cl], first = boff[2 * e + cl];
@@ -149,7 +162,7 @@ __global__ __launch_bounds__(kPermBlock) void perm_fused(const int32_t *__restri
                                                          int32_t *__restrict__ off, int32_t *__restrict__ perm,
                                                          int32_t *__restrict__ inv, uint8_t *__restrict__ cls,
                                                          moe_unit *__restrict__ units, int32_t *__restrict__ n_units,
-                                                         int max_units) {
+                                                         int max_units, int32_t *__restrict__ report, int32_t seq) {
     extern __shared__ int32_t sm[];
     const int nb = 2 * E, tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     int32_t *tot = sm, *boff = sm + nb, *ustart = sm + 2 * nb, *tmp = sm + 3 * nb, *running = sm + 4 * nb;
@@ -175,6 +188,7 @@ __global__ __launch_bounds__(kPermBlock) void perm_fused(const int32_t *__restri
     __syncthreads();
     const int nu = block_excl_scan(ustart, tmp, nb);
     if (tid == 0) *n_units = nu;
+    report_to_host(report, seq, tot, nb, nu);
     for (int q = tid; q < nb; q += kPermBlock) {
         const int cl = q / E, e = q - cl * E;
         const int len = tot[2 * e + cl], first = boff[2 * e + cl];
@@ -235,13 +249,13 @@ hipError_t launch_permute(const PermuteArgs &a, hipStream_t s) {
     if (A <= kPermFusedMax) {
         hipLaunchKernelGGL(perm_fused, dim3(1), dim3(kPermBlock), (size_t)(5 + 16) * nb * sizeof(int32_t), s, a.topk_idx,
                            a.prio, A, a.k, a.E, a.C, nbits, a.cnt, a.off, a.perm, a.inv, a.cls, a.units, a.n_units,
-                           a.max_units);
+                           a.max_units, a.report, a.seq);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(perm_rank, dim3(nblocks), dim3(kPermBlock), (size_t)16 * nb * sizeof(int32_t), s, a.topk_idx,
                        a.prio, A, a.k, nb, nbits, a.rank, a.blockoff, a.cls);
     hipLaunchKernelGGL(perm_scan, dim3(1), dim3(1024), 0, s, a.blockoff, nblocks, a.E, a.C, a.cnt, a.off, a.units,
-                       a.n_units, a.max_units);
+                       a.n_units, a.max_units, a.report, a.seq);
     hipLaunchKernelGGL(perm_scatter, dim3((A + 255) / 256), dim3(256), 0, s, a.topk_idx, a.prio, A, a.k, nb, a.rank,
                        (const int32_t *)a.blockoff, (const int32_t *)a.off, a.perm, a.inv);
     return hipGetLastError();

@@ -6,6 +6,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <climits>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -29,6 +32,7 @@ int32_t hip_fail(hipError_t e, const char *what) {
 }
 
 constexpr size_t kAlign = 256;
+constexpr int kReportSpinMs = 200;   // how long moe_permute polls for the kernel's report before it waits for the stream
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 bool config_ok(const moe_config *c, const char **why) {
@@ -113,7 +117,10 @@ struct moe_ctx {
     std::vector<uint32_t> unmarked;            // executed units whose rows are not yet flagged on the device
     bool done_valid;                           // the device flags of this layer-batch have been cleared
     std::vector<int32_t> cnt;
-    int32_t *pinned;  // 2E counts + 1 unit count, pinned host memory (allocated at first route)
+    int32_t *pinned;  // 2E counts, unit count, sequence word: pinned host memory mapped into the device
+                      // (allocated at first route); the permutation kernels write it directly
+    int32_t *pinned_dev;   // the device's address of the same memory
+    int32_t seq;           // sequence number of the last report asked for
     const void *x;
     moe_weights w;
     qmoe::Profiler prof;
@@ -216,6 +223,8 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->next_unit = c->n_units = c->n_ls_units = c->n_done = c->n_ls_done = 0;
     c->done_valid = false;
     c->pinned = nullptr;
+    c->pinned_dev = nullptr;
+    c->seq = 0;
     c->prof_on = false;
     c->x = nullptr;
     c->w = moe_weights{};
@@ -244,8 +253,16 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     if (w->layout == MOE_W_MXFP4 && (!w->S1 || !w->S3 || !w->S2)) return fail(MOE_E_ARG, "moe_route: 4-bit weights need the scale pointers S1, S3, S2");
     if (n_tokens > 0 && !x) return fail(MOE_E_ARG, "moe_route: null x");
     if (!ctx->pinned) {
-        hipError_t e = hipHostMalloc((void **)&ctx->pinned, (2 * (size_t)ctx->cfg.E + 1) * sizeof(int32_t), hipHostMallocDefault);
+        const size_t words = 2 * (size_t)ctx->cfg.E + 2;
+        hipError_t e = hipHostMalloc((void **)&ctx->pinned, words * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { ctx->pinned = nullptr; return hip_fail(e, "moe_route: hipHostMalloc"); }
+        e = hipHostGetDevicePointer((void **)&ctx->pinned_dev, ctx->pinned, 0);
+        if (e != hipSuccess) {
+            (void)hipHostFree(ctx->pinned);
+            ctx->pinned = nullptr;
+            return hip_fail(e, "moe_route: hipHostGetDevicePointer");
+        }
+        memset(ctx->pinned, 0, words * sizeof(int32_t));
     }
     if (n_tokens > 0) {
         qmoe::RouteArgs a{};
@@ -294,11 +311,28 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
         a.units = at<moe_unit>(ctx, ctx->lay.units);
         a.n_units = at<int32_t>(ctx, ctx->lay.n_units);
         a.max_units = (int32_t)ctx->lay.max_units;
+        ctx->seq = ctx->seq == INT32_MAX ? 1 : ctx->seq + 1;
+        a.report = ctx->pinned_dev;
+        a.seq = ctx->seq;
         hipError_t e = qmoe::launch_permute(a, s);
         if (e != hipSuccess) return hip_fail(e, "moe_permute: launch");
-        e = hipMemcpyAsync(ctx->pinned, a.cnt, (2 * (size_t)E + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s);
-        if (e == hipSuccess) e = hipStreamSynchronize(s);
-        if (e != hipSuccess) return hip_fail(e, "moe_permute: reading the counts back");
+        // The kernel stores the counts, the unit count and then the sequence word into host memory as
+        // soon as it knows them; wait for that word (bounded: after kReportSpinMs fall back to waiting
+        // for the stream, which also surfaces a failed launch).
+        volatile int32_t *word = ctx->pinned + 2 * E + 1;
+        const auto t0 = std::chrono::steady_clock::now();
+        bool seen = false;
+        for (unsigned spins = 0;; ++spins) {
+            if (*word == ctx->seq) { seen = true; break; }
+            if ((spins & 1023u) == 1023u &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(kReportSpinMs)) break;
+        }
+        if (!seen) {
+            e = hipStreamSynchronize(s);
+            if (e != hipSuccess) return hip_fail(e, "moe_permute: waiting for the counts");
+            if (*word != ctx->seq) return fail(MOE_E_HIP, "moe_permute: the permutation kernel did not report its counts");
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
         ctx->cnt.assign(ctx->pinned, ctx->pinned + 2 * E);
     } else {
         hipError_t e = hipMemsetAsync(at<void>(ctx, ctx->lay.cnt), 0, (2 * (size_t)E + 1) * 4, s);

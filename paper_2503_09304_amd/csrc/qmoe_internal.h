@@ -54,6 +54,8 @@ struct PermuteArgs {
     moe_unit *units;    // device unit list
     int32_t *n_units;   // device scalar
     int32_t max_units;
+    int32_t *report;    // host memory mapped into the device: counts [2E], unit count, sequence word
+    int32_t seq;        // value the kernel stores into the sequence word once the report is written
 };
 hipError_t launch_permute(const PermuteArgs &a, hipStream_t s);
 
