@@ -55,7 +55,7 @@ def pct(v, p):
     return float(np.percentile(np.asarray(v), p))
 
 
-def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, seed=77):
+def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be_ksplit=0, seed=77):
     """LS completion latency when a BE prompt is in flight (cfg3): the BE context is fed
     `units_per_call` work units per moe_expert_run with at most `lookahead` calls outstanding; at a
     seeded offset into the BE layer an LS batch arrives, the host stops feeding BE, runs the LS
@@ -63,7 +63,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, se
     LS combine finished."""
     import numpy as np
     cbe, cls_ = wl.CONFIGS["cfg3_be"], wl.CONFIGS["cfg3_ls"]
-    be = GpuLayer(wl.make_inputs(cbe, weights={}), dw)
+    be = GpuLayer(wl.make_inputs(cbe, weights={}), dw, down_ksplit=be_ksplit)
     ls = GpuLayer(wl.make_inputs(cls_, weights={}), dw)
 
     def run_ls():
@@ -88,11 +88,30 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, se
         t.append(time.perf_counter() - t0)
     ls_alone_ms = 1e3 * float(np.median(t))
 
+    # the BE layer fed the preemptible way (bounded look-ahead), nothing arriving: what being
+    # stoppable at every chunk costs in BE throughput
+    def feed_be():
+        be.route_permute()
+        pending, done = [], False
+        while not done:
+            while pending and pending[0].query():
+                pending.pop(0)
+            if len(pending) < lookahead:
+                done = be.run(units_per_call) == q.MOE_DONE
+                ev = torch.cuda.Event(); ev.record(); pending.append(ev)
+        be.combine()
+    t = []
+    for _ in range(5):
+        torch.cuda.synchronize(); t0 = time.perf_counter(); feed_be(); torch.cuda.synchronize()
+        t.append(time.perf_counter() - t0)
+    be_fed_ms = 1e3 * min(t)
+
     rng = np.random.default_rng(seed)
-    offsets = rng.uniform(0.02, 0.95, size=trials) * be_ms * 1e-3
+    fractions = rng.uniform(0.02, 0.95, size=trials)     # arrival point as a fraction of the BE layer's duration
     lat, lat_nopre, waited_units, identical = [], [], [], True
-    for i, off in enumerate(offsets):
+    for i, frac in enumerate(fractions):
         # --- run-to-completion baseline: the BE layer is enqueued whole; LS waits behind it
+        off = frac * be_ms * 1e-3
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run_be_all()
@@ -102,6 +121,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, se
         torch.cuda.synchronize()
         lat_nopre.append(time.perf_counter() - (t0 + off))
         # --- preemptive: bounded look-ahead, stop at the next expert-chunk boundary
+        off = frac * be_fed_ms * 1e-3
         be.y.fill_(float("nan"))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -141,6 +161,8 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, se
         "ls_alone_idle_gpu_ms": round(ls_alone_ms, 4),
         "ls_latency_no_preemption_ms": {"p50": ms(pct(lat_nopre, 50)), "p99": ms(pct(lat_nopre, 99))},
         "be_layer_uninterrupted_ms": round(be_ms, 4),
+        "be_layer_fed_with_lookahead_ms": round(be_fed_ms, 4),
+        "be_down_ksplit": be_ksplit,
         "be_units_enqueued_at_arrival_mean": round(float(np.mean(waited_units)), 2) if waited_units else 0.0,
         "be_output_bit_identical_after_resume": identical,
     }
@@ -219,8 +241,10 @@ def main() -> int:
                     help="expert weight format: bf16 (the headline workload) or 4-bit microscaling FP4")
     ap.add_argument("--latency-trials", type=int, default=40,
                     help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
-    ap.add_argument("--units-per-call", type=int, default=1)
-    ap.add_argument("--lookahead", type=int, default=2)
+    ap.add_argument("--units-per-call", type=int, default=4)
+    ap.add_argument("--lookahead", type=int, default=1)
+    ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 4],
+                    help="down_ksplit of the BE context in the latency scenario (0 = from the configuration)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the yardstick for HBM byte counters")
     args = ap.parse_args()
@@ -339,7 +363,8 @@ def main() -> int:
     # ---- LS latency while a long BE batch is in flight (Mixtral weights)
     lat = None
     if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx:
-        lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead)
+        lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
+                         be_ksplit=args.be_ksplit)
         log("LS latency under BE load:", json.dumps(lat))
 
     # ---- the oracle, as it stands, on a bounded sample of the same workload

@@ -71,7 +71,10 @@ class _Slot:
     """Buffers and context of one in-flight batch of one stage."""
 
     def __init__(self, E, k, H, F, chunk_rows, max_tokens, device):
-        self.ctx = q.Context(E, k, H, F, q.MOE_BF16, chunk_rows, max_tokens, device=device)
+        # Batches are fed a few chunks at a time when they must stay stoppable; the K-split down
+        # projection keeps such small launches wide enough to use the chip.
+        self.ctx = q.Context(E, k, H, F, q.MOE_BF16, chunk_rows, max_tokens, device=device,
+                             down_ksplit=4 if F % 256 == 0 else 0)
         self.x = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
         self.y = torch.empty((max_tokens, H), dtype=torch.bfloat16, device=device)
         self.prio = torch.empty(max_tokens, dtype=torch.uint8, device=device)
@@ -81,7 +84,7 @@ class _Slot:
 
 class Engine:
     def __init__(self, weights: q.MoeWeights, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
-                 max_prompt: int, preemptive: bool, units_per_call: int = 2, lookahead: int = 2, chunk_rows: int = 256,
+                 max_prompt: int, preemptive: bool, units_per_call: int = 4, lookahead: int = 1, chunk_rows: int = 256,
                  bank_rows: int = 4096, seed: int = 1, digest: bool = False, device="cuda:0"):
         self.w, self.layers, self.batch_size, self.max_prompt = weights, layers, batch_size, max_prompt
         self.preemptive, self.units_per_call, self.lookahead = preemptive, units_per_call, lookahead
