@@ -67,7 +67,10 @@ typedef struct {
     int32_t down_ksplit; /* K-split of the down projection: 0 = choose from the configuration, 1 = none,
                             4 = four K quarters added in a fixed order (bf16, F % 256 == 0 only).
                             0 picks 4 when F % 256 == 0 and max_tokens*k <= 256*E (weight-streaming
-                            shapes, where the split supplies the parallelism), else 1.  Part of the
+                            shapes, where the split supplies the parallelism), else 1.  Choose 4 for a
+                            context whose batches are fed a few units per call so that they can be
+                            stopped quickly: a launch of few units has only H/256 workgroups per unit in
+                            the down projection without the split.  Part of the
                             configuration, never of a launch: results of one context do not depend on it
                             changing, because it cannot change.                                          */
 } moe_config;

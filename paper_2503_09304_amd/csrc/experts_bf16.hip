@@ -1,5 +1,7 @@
 // bf16 expert path: launch dispatch, the plane reduction of the K-split down projection, and the
 // weight re-layout kernel.  The GEMM kernels themselves are the templates of experts_bf16_tile.h.
+#include <vector>
+
 #include "experts_bf16_tile.h"
 
 namespace qmoe {
@@ -106,11 +108,24 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
         bool shared = false;
         for (int i = 1; i < a.nseg; ++i) shared = shared || a.segs[i].expert == a.segs[i - 1].expert;
         if (shared) {
-            for (int i = 0; i < a.nseg && n <= kMaxSegs; ++i) {
-                if (i > 0 && a.segs[i].expert != a.segs[i - 1].expert)
-                    while ((n & 3) && n < kMaxSegs) b.seg[n++] = Seg{0, 0, a.segs[i - 1].expert};
-                if (n < kMaxSegs) b.seg[n] = a.segs[i];
-                ++n;
+            // experts in descending order of their rows in this launch (the order of experts is free:
+            // the busiest ones start first, the small ones fill the tail), each expert's segments
+            // kept together and in row order
+            struct Group { int first, count, rows; };
+            std::vector<Group> groups;
+            for (int i = 0; i < a.nseg; ++i) {
+                if (i == 0 || a.segs[i].expert != a.segs[i - 1].expert) groups.push_back(Group{i, 0, 0});
+                groups.back().count += 1;
+                groups.back().rows += a.segs[i].rows;
+            }
+            std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.rows > y.rows; });
+            for (const Group &g : groups) {
+                while ((n & 3) && n < kMaxSegs) b.seg[n++] = Seg{0, 0, 0};
+                for (int i = g.first; i < g.first + g.count; ++i) {
+                    if (n < kMaxSegs) b.seg[n] = a.segs[i];
+                    ++n;
+                }
+                if (n > kMaxSegs) break;
             }
         }
         if (!shared || n > kMaxSegs) {
