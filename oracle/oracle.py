@@ -214,10 +214,13 @@ def mxfp4_weights_as_bf16(w: dict) -> dict:
     element * scale is exactly representable in bf16, which is asserted."""
     out = {"Wg": w["Wg"]}
     for n in ("W1", "W3", "W2"):
-        v = dequant_mxfp4(w[n + "q"], w[n + "s"]).astype(np.float32)
-        bits = v.view(np.uint32)
-        assert not (bits & 0xFFFF).any()
-        out[n] = (bits >> 16).astype(np.uint16)
+        codes, scales = w[n + "q"], w[n + "s"]
+        dst = np.empty(codes.shape[:-1] + (codes.shape[-1] * 2,), dtype=np.uint16)
+        for e in range(codes.shape[0]):          # expert by expert: the fp64 temporaries stay small
+            bits = dequant_mxfp4(codes[e], scales[e]).astype(np.float32).view(np.uint32)
+            assert not (bits & 0xFFFF).any()
+            dst[e] = (bits >> 16).astype(np.uint16)
+        out[n] = dst
     return out
 
 

@@ -93,3 +93,27 @@ def test_cfg5_fine_grained_skewed_with_four_preemptions():
     cuts = wl.cut_points(cfg.seed, expert_boundaries(units), 4)
     assert len(cuts) == 4
     assert_bit_identical(inp, cuts, base=g)
+
+
+def test_cfg4_decode_with_4bit_weights_full_size():
+    """The decode workload with 4-bit expert weights at the Mixtral shape, as bench.py --weights mxfp4
+    times it: every token against the oracle's reading of the same codes, and one unit per call."""
+    from gpu_util import DevWeightsMX
+    cfg = wl.CONFIGS["cfg4"]
+    w4 = wl.make_weights_mxfp4(cfg)
+    inp = wl.make_inputs(cfg, weights=oracle.mxfp4_weights_as_bf16(w4))
+    mx = DevWeightsMX(w4).packed()
+    g = GpuLayer(inp, mx).full()
+    r = g.fetch("logits", "topk_idx", "counts", "perm", "y")
+    lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows, logits=r["logits"].astype(np.float64))
+    assert np.array_equal(r["topk_idx"], lay.idx) and np.array_equal(r["counts"], lay.cnt) and np.array_equal(r["perm"], lay.perm)
+    toks = np.arange(cfg.N)
+    y_ref = lay.y_tokens_direct(toks)
+    e = rel_err(wl.as_f64(r["y"]), y_ref)
+    floor = rel_err(wl.as_f64(wl.f32_to_bf16_bits(y_ref.astype(np.float32))), y_ref)
+    tol = max(2e-2, floor + 1.2e-2)
+    say(f"  cfg4 with 4-bit weights: y rel err {e:.3e} (tol {tol:.3e}; bf16 output rounding alone {floor:.3e})")
+    assert e <= tol
+    nu = g.ctx.cursor.n_units
+    h = GpuLayer(inp, mx).full(tuple(range(1, nu)))
+    assert torch.equal(bits(h.y), bits(g.y))
