@@ -81,3 +81,36 @@ def test_error_behaviour():
     assert s.next_batch() == ([7], q.SCHED_PREFILL, 0)
     assert s.next_batch() is None
     assert s.running() == 1
+
+
+def replay_fixture(path, make):
+    """Run a tests/golden scheduler script against a scheduler object with the oracle's method names."""
+    s = None
+    for raw in open(path):
+        line = raw.split("#")[0].strip()
+        if not line:
+            continue
+        f = line.split()
+        if f[0] == "batch_size":
+            s = make(int(f[1]))
+        elif f[0] == "submit":
+            s.submit(int(f[1]), q.SCHED_LS if f[2] == "LS" else q.SCHED_BE)
+        elif f[0] == "token":
+            s.token(int(f[1]), f[2] == "last")
+        elif f[0] == "preempt?":
+            assert s.preempt_wanted(int(f[1])) == (f[2] == "yes"), line
+        elif f[0] == "batch":
+            stage = q.SCHED_PREFILL if f[1] == "PREFILL" else q.SCHED_DECODE
+            got = s.next_batch()
+            assert got is not None and (list(got[0]), got[1], got[2]) == ([int(v) for v in f[4:]], stage, int(f[2])), line
+        elif f[0] == "none":
+            assert s.next_batch() is None
+        else:
+            raise ValueError(line)
+
+
+def test_paper_example_sequence_on_both_schedulers():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "fig_architecture_example.txt")
+    replay_fixture(path, SchedOracle)
+    replay_fixture(path, q.Scheduler)
