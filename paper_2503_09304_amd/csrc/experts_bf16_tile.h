@@ -168,7 +168,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 
     // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
     // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
-    constexpr int DA = T >= 8 ? 1 : D;   // token pieces: same distance, or 1 where registers are scarce
+    constexpr int DA = T >= 7 ? 1 : D;   // token pieces: same distance, or 1 where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
     bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]; MXFP4: set 0 only, the operands of the current iteration
@@ -407,7 +407,7 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
 }
 
 // TCAP: largest number of 32-token tiles a segment of this launch may have (1, 2, 4, 6 or 8).  A
-// workgroup takes the smallest fully unrolled variant (1, 2, 4, 5, 6 or 8 tiles) that covers its unit.
+// workgroup takes the smallest fully unrolled variant (1, 2, 4, 5, 6, 7 or 8 tiles) that covers its unit.
 // STREAM: no two segments of the launch belong to one expert, so every weight element is read by
 // exactly one workgroup: the loads carry the non-temporal hint and do not displace the token tiles
 // in L2.  Where segments share an expert's weights the hint is left off so that L2 serves the re-reads.
@@ -420,7 +420,8 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     if (!map_block(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
-    if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    if (TCAP >= 8 && t_cnt > 7) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 7 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 5 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);

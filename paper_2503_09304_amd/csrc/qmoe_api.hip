@@ -394,17 +394,31 @@ static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, 
             if (un[p].expert != un[q].expert) return un[p].expert < un[q].expert;
             return un[p].row0 < un[q].row0;
         });
-        std::vector<qmoe::Seg> segs;
+        // First the runs of row-adjacent units of one expert, then each run cut into ceil(rows/256)
+        // segments of (nearly) equal numbers of 32-row tiles: workgroups that share an expert's weight
+        // tiles then advance through K at the same pace and meet in L2, which a 256/256/256/128 cut
+        // does not give them.
+        struct Run { uint32_t row0, rows; uint16_t expert; };
+        std::vector<Run> runs;
         for (uint32_t i : idx) {
             const moe_unit &u = un[i];
-            if (!segs.empty()) {
-                qmoe::Seg &b = segs.back();
-                if (b.expert == (uint16_t)u.expert && b.row0 + b.rows == (uint32_t)u.row0 && b.rows + u.rows <= 256) {
-                    b.rows = (uint16_t)(b.rows + u.rows);
-                    continue;
-                }
+            if (!runs.empty() && runs.back().expert == (uint16_t)u.expert && runs.back().row0 + runs.back().rows == (uint32_t)u.row0)
+                runs.back().rows += (uint32_t)u.rows;
+            else
+                runs.push_back(Run{(uint32_t)u.row0, (uint32_t)u.rows, (uint16_t)u.expert});
+        }
+        std::vector<qmoe::Seg> segs;
+        for (const Run &r : runs) {
+            const uint32_t nseg = (r.rows + 255) / 256, tiles = (r.rows + 31) / 32;
+            const uint32_t base = tiles / nseg, extra = tiles % nseg;
+            uint32_t row = r.row0, left = r.rows;
+            for (uint32_t j = 0; j < nseg; ++j) {
+                const uint32_t want = (base + (j < extra ? 1 : 0)) * 32;
+                const uint32_t take = want < left ? want : left;
+                segs.push_back(qmoe::Seg{row, (uint16_t)take, r.expert});
+                row += take;
+                left -= take;
             }
-            segs.push_back(qmoe::Seg{(uint32_t)u.row0, (uint16_t)u.rows, (uint16_t)u.expert});
         }
         if (segs.size() > (size_t)qmoe::kMaxSegs && contiguous) {
             // too many segments for the kernel arguments: the launch reads the device unit list
