@@ -326,7 +326,8 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     // ---- epilogue.  D register r of lane l: token 8*(r/4) + 4*(l/32) + r%4, weight row l%32 ----
     if (GATEUP) {
         // SwiGLU in fp32, one rounding to bf16; the wave's [T*32 tokens][32 f] tile goes through LDS
-        // (free after the last barrier of the main loop) so that it leaves as 16-byte stores.
+        // (free after the last barrier of the main loop) so that it leaves as 16-byte stores, with the
+        // non-temporal hint: the next kernel reads it, nothing in this one does.
         __bf16 *st = reinterpret_cast<__bf16 *>(lds) + w * (ROWS * 32);
         static_for<T>([&](auto tc) {
             constexpr int t = decltype(tc)::value;
@@ -344,7 +345,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
             const int i = (l >> 2) + 16 * j;
             if (i < rows && f0 < p.ncols) {
                 const u32x4 v = *reinterpret_cast<const u32x4 *>(st + i * 32 + (l & 3) * 8);
-                *reinterpret_cast<u32x4 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + f0) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + f0));
             }
         }
     } else {
@@ -369,7 +370,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
                 for (int j = 0; j < 8; ++j) {
                     const int i = (l >> 4) + 4 * j;
                     const f32x4 v = *reinterpret_cast<const f32x4 *>(st + i * 64 + (l & 15) * 4);
-                    if (t * 32 + i < rows && col_ok) *reinterpret_cast<f32x4 *>(obase + (long)(t * 32 + i) * p.ldd) = v;
+                    if (t * 32 + i < rows && col_ok) __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(obase + (long)(t * 32 + i) * p.ldd));
                 }
                 __builtin_amdgcn_s_waitcnt(0xc07f);
             }
