@@ -12,6 +12,8 @@
 namespace qmoe {
 namespace {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 // done == nullptr: tokens are selected by class (the host has checked that the class is finished).
 // done != nullptr: a token is selected when done[] is set for all k of its sorted positions;
 // complete[n] (if given) reports the selection.
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ ou
         for (int h = threadIdx.x * 4; h < H; h += 1024) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int j = 0; j < k; ++j) {
-                const float4 v = *reinterpret_cast<const float4 *>(out + (long)sp[j] * H + h);
+                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(out + (long)sp[j] * H + h));   // read once
                 const float wj = sw[j];
                 acc.x = fmaf(wj, v.x, acc.x);
                 acc.y = fmaf(wj, v.y, acc.y);
