@@ -385,13 +385,25 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 // a long queue, or its LS and BE part), the 8 weight tiles by up to 4.  Packet q goes to XCD q % 8;
 // the workgroups of a packet get ids 8 apart.  With a K-split the column-tile axis is
 // (quarter, tile), quarter slowest, so a packet stays inside one quarter.
+template <bool STREAM>
 __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct, int &kq) {
     const int w = blockIdx.x;
     const int x = w & 7, j = w >> 3;
     const int packet = (j >> 5) * 8 + x, within = j & 31;
     const int n = b.nseg > 0 ? b.nseg : b.k.nu;
     const int ugroups = (n + 3) >> 2;
-    const int ctb = packet / ugroups, ug = packet - ctb * ugroups;
+    // Streaming launches list their segments longest first: the packets walk the column tiles of one
+    // group of segments before the next group, so the long segments really start first.  Launches
+    // that share weights walk the groups first: the packets of one column block run side by side.
+    int ctb, ug;
+    if (STREAM) {
+        const int ctbs = (b.k.col_tiles * b.ksplit + 7) >> 3;
+        ug = packet / ctbs;
+        ctb = packet - ug * ctbs;
+    } else {
+        ctb = packet / ugroups;
+        ug = packet - ctb * ugroups;
+    }
     const int pos = ug * 4 + (within >> 3);
     const int cq = ctb * 8 + (within & 7);
     if (pos >= n || cq >= b.k.col_tiles * b.ksplit) return false;
@@ -418,7 +430,7 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     __shared__ __attribute__((aligned(16))) char lds[(2 * TCAP * 32 * 128) > 32768 ? (2 * TCAP * 32 * 128) : 32768];
     int ct, kq;
     moe_unit un;
-    if (!map_block(b, un, ct, kq)) return;
+    if (!map_block<STREAM>(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
     if (TCAP >= 8 && t_cnt > 7) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
