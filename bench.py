@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2027180478, "cfg4": 1910700787, "cfg3_be": 5326678046, "cfg5": 3317011655,
-                          "cfg4_mxfp4": 514426640, "cfg3_be_mxfp4": 1895361050}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2019327730, "cfg4": 1913119136, "cfg3_be": 3650022154, "cfg5": 2704743648,
+                          "cfg4_mxfp4": 516125213, "cfg3_be_mxfp4": 1542261805}
 
 
 def log(*a):
