@@ -106,8 +106,22 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         t.append(time.perf_counter() - t0)
     be_fed_ms = 1e3 * min(t)
 
+    # the BE layer enqueued whole as gated launches (moe_expert_enqueue), nothing arriving
+    def enqueue_be():
+        be.route_permute()
+        while be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call) != q.MOE_DONE:
+            if be.ctx.expert_collect() == q.MOE_DONE:
+                break
+        be.combine()
+    t = []
+    for _ in range(5):
+        torch.cuda.synchronize(); t0 = time.perf_counter(); enqueue_be(); torch.cuda.synchronize()
+        t.append(time.perf_counter() - t0)
+    be_enq_ms = 1e3 * min(t)
+
     rng = np.random.default_rng(seed)
     fractions = rng.uniform(0.02, 0.95, size=trials)     # arrival point as a fraction of the BE layer's duration
+    lat_dev, identical_dev = [], True
     lat, lat_nopre, waited_units, identical = [], [], [], True
     for i, frac in enumerate(fractions):
         # --- run-to-completion baseline: the BE layer is enqueued whole; LS waits behind it
@@ -153,6 +167,28 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         lat.append(t_done - off)
         if i < 8:
             identical = identical and bool(torch.equal(be.y.view(torch.int16), y_ref.view(torch.int16)))
+        # --- device-side stop: the whole BE layer is on the stream as gated launches; at the arrival the
+        # host sets the stop word and enqueues the LS batch behind whatever still runs
+        off = frac * be_enq_ms * 1e-3
+        be.y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        be.route_permute()
+        rc = be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call)
+        while time.perf_counter() - t0 < off:
+            pass
+        be.ctx.expert_stop()
+        run_ls()
+        ev = torch.cuda.Event(); ev.record(); ev.synchronize()
+        lat_dev.append(time.perf_counter() - t0 - off)
+        while rc != q.MOE_DONE:
+            rc = be.ctx.expert_collect()
+            if rc != q.MOE_DONE:
+                rc = be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call)
+        be.combine()
+        torch.cuda.synchronize()
+        if i < 8:
+            identical_dev = identical_dev and bool(torch.equal(be.y.view(torch.int16), y_ref.view(torch.int16)))
     ms = lambda v: round(1e3 * v, 4)
     return {
         "workload": "cfg3: 3584-token BE prompt in flight (28 units of <=256 rows), 512-token LS batch arrives",
@@ -163,6 +199,9 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         "be_layer_uninterrupted_ms": round(be_ms, 4),
         "be_layer_fed_with_lookahead_ms": round(be_fed_ms, 4),
         "be_down_ksplit": be_ksplit,
+        "device_stop": {"ls_latency_ms": {"p50": ms(pct(lat_dev, 50)), "p99": ms(pct(lat_dev, 99)), "max": ms(max(lat_dev))},
+                        "be_layer_enqueued_ms": round(be_enq_ms, 4), "units_per_launch": units_per_call,
+                        "be_output_bit_identical_after_resume": identical_dev},
         "be_units_enqueued_at_arrival_mean": round(float(np.mean(waited_units)), 2) if waited_units else 0.0,
         "be_output_bit_identical_after_resume": identical,
     }

@@ -9,8 +9,8 @@
  *
  * One layer-batch goes through
  *
- *     moe_route -> moe_permute -> moe_expert_run / moe_expert_run_units (any number of calls)
- *               -> moe_combine / moe_combine_complete
+ *     moe_route -> moe_permute -> moe_expert_run / moe_expert_run_units (any number of calls),
+ *               or moe_expert_enqueue .. moe_expert_collect -> moe_combine / moe_combine_complete
  *
  * Every return of moe_expert_run is a preemption point: the caller may run other contexts (for
  * instance a newly arrived LS batch) before calling it again with the saved cursor.
@@ -204,6 +204,25 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
  * moe_expert_run can carry on from it.  Returns MOE_OK while units remain, MOE_DONE when all ran. */
 int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, const uint32_t *unit_ids,
                              uint32_t n, moe_cursor *cursor, void *stream);
+
+/* Expert work enqueued ahead and stopped from the device side (Sec. 5 "Overlapping preemption with execution":
+ * named there as future work).  moe_expert_enqueue puts ALL units that have
+ * not run yet on the stream, as launches of units_per_launch units each, and returns without waiting.
+ * In front of every launch a one-thread gate kernel reads the context's stop word (host memory mapped
+ * into the device): while it is clear the launch runs in full; once it is set, that launch and every
+ * later one of the sequence do nothing.  No kernel waits or spins.  moe_expert_stop sets the stop word
+ * (a plain host store; may be called from another thread than the one that enqueued).  Work of other
+ * contexts may be enqueued on the stream at any time; it runs behind whatever the sequence still
+ * executes (at most the launch in progress plus the empty shells of the rest).
+ * moe_expert_collect waits for the stream, reads how many launches ran in full, books their units as
+ * executed, clears the stop word and returns the cursor in *cursor ([host]); MOE_DONE if every unit
+ * has run, MOE_OK otherwise (then carry on with moe_expert_enqueue or moe_expert_run).  A launch
+ * either ran completely or not at all, and its arithmetic is that of moe_expert_run, bit for bit.
+ * Between enqueue and collect every other call on the context fails with MOE_E_STATE. */
+int32_t moe_expert_enqueue(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t units_per_launch,
+                           void *stream);
+int32_t moe_expert_stop(moe_ctx *ctx);
+int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream);
 
 /* Gate-weighted combine of complete tokens (Sec. 3.1: only fully processed tokens contribute to
  * the next layer's hidden state):

@@ -84,6 +84,9 @@ def lib():
         L.moe_expert_run_units.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.POINTER(C.c_uint32),
                                            C.c_uint32, C.POINTER(MoeCursor), C.c_void_p]
         L.moe_combine_complete.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.moe_expert_enqueue.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.c_uint32, C.c_void_p]
+        L.moe_expert_stop.argtypes = [C.c_void_p]
+        L.moe_expert_collect.argtypes = [C.c_void_p, C.POINTER(MoeCursor), C.c_void_p]
         L.moe_get.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]
         L.moe_units.argtypes = [C.c_void_p, C.POINTER(MoeUnit), C.c_uint32, C.POINTER(C.c_uint32)]
         L.moe_plan_units.argtypes = [C.POINTER(C.c_int32), C.c_int32, C.c_int32, C.POINTER(MoeUnit), C.c_uint32,
@@ -91,7 +94,7 @@ def lib():
         L.moe_pack_weights.argtypes = [C.POINTER(MoeConfig), C.POINTER(MoeWeights), C.POINTER(MoeWeights), C.c_void_p]
         L.moe_profile.argtypes = [C.c_void_p, C.c_int32]
         L.moe_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_uint32)]
-        for f in ("moe_expert_run_units", "moe_combine_complete", "moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
+        for f in ("moe_expert_enqueue", "moe_expert_stop", "moe_expert_collect", "moe_expert_run_units", "moe_combine_complete", "moe_pack_weights", "moe_profile", "moe_profile_read", "moe_create", "moe_destroy", "moe_route", "moe_permute", "moe_expert_run", "moe_combine",
                   "moe_get", "moe_units", "moe_plan_units"):
             getattr(L, f).restype = C.c_int32
         # include/qsched.h
@@ -214,6 +217,18 @@ class Context:
         arr = (C.c_uint32 * max(1, len(ids)))(*ids)
         return _check(lib().moe_expert_run_units(self.h, _ptr(x), C.byref(w), arr, len(ids), C.byref(self.cursor),
                                                  _stream()))
+
+    def expert_enqueue(self, x, w: MoeWeights, units_per_launch: int = 4) -> int:
+        """Put all remaining units on the stream as gated launches; returns without waiting."""
+        return _check(lib().moe_expert_enqueue(self.h, _ptr(x), C.byref(w), units_per_launch, _stream()))
+
+    def expert_stop(self) -> None:
+        """Ask the enqueued sequence to stop at its next launch boundary."""
+        _check(lib().moe_expert_stop(self.h))
+
+    def expert_collect(self) -> int:
+        """Wait for the stream and book what ran; updates self.cursor.  MOE_DONE when every unit has run."""
+        return _check(lib().moe_expert_collect(self.h, C.byref(self.cursor), _stream()))
 
     def combine_complete(self, y, complete=None) -> int:
         """Write the rows of y of every token whose k assignments have all been executed; `complete`

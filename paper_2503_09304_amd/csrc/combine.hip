@@ -87,7 +87,25 @@ __global__ __launch_bounds__(256) void clear_bytes(uint8_t *__restrict__ p, long
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = 0;
 }
 
+__global__ void gate_kernel(const int32_t *__restrict__ stop_host, int32_t *__restrict__ completed_host,
+                            int32_t *__restrict__ go, int g, int n_launches) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const int prev_open = g == 0 ? 1 : go[g - 1];
+    if (g > 0 && prev_open) {
+        __hip_atomic_store(completed_host, g, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (g < n_launches) {
+        const int stop = __hip_atomic_load(stop_host, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        go[g] = (prev_open && stop == 0) ? 1 : 0;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_gate(const int32_t *stop_host, int32_t *completed_host, int32_t *go, int g, int n_launches, hipStream_t s) {
+    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, stop_host, completed_host, go, g, n_launches);
+    return hipGetLastError();
+}
 
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s) {
     if (a.N <= 0) return hipSuccess;

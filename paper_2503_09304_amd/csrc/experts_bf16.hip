@@ -12,6 +12,7 @@ using bf16k::f32x4;
 
 // out[r,:] = ((p0 + p1) + p2) + p3 for the rows of the launch.
 __global__ __launch_bounds__(256) void reduce_planes(const BArgs b, const float *__restrict__ part, float *__restrict__ out, int H) {
+    if (b.k.go != nullptr && *b.k.go == 0) return;
     const long plane = b.plane;
     moe_unit un;
     if (b.nseg > 0) {

@@ -428,6 +428,7 @@ template <int TCAP, bool GATEUP, int WF, bool STREAM>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     // two token-tile stages; at least 8 KiB per wave for the epilogue's store staging
     __shared__ __attribute__((aligned(16))) char lds[(2 * TCAP * 32 * 128) > 32768 ? (2 * TCAP * 32 * 128) : 32768];
+    if (b.k.go != nullptr && *b.k.go == 0) return;      // a closed gate: this launch is skipped as a whole
     int ct, kq;
     moe_unit un;
     if (!map_block<STREAM>(b, un, ct, kq)) return;

@@ -19,6 +19,7 @@ struct KArgs {
     unsigned u0;
     int nu;                 // units in this launch
     int col_tiles;
+    const int32_t *go;      // gated launches: the workgroups do nothing unless *go != 0 (nullptr: not gated)
 };
 
 struct Scope {

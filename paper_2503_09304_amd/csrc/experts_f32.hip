@@ -13,6 +13,7 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 template <bool GATEUP>
 __global__ __launch_bounds__(256) void expert_f32(const KArgs p, int row_tiles) {
+    if (p.go != nullptr && *p.go == 0) return;
     __shared__ float As[16][65];
     __shared__ float B0s[16][65];
     __shared__ float B1s[GATEUP ? 16 : 1][65];

@@ -58,7 +58,7 @@ bool config_ok(const moe_config *c, const char **why) {
 
 // Offsets of the workspace regions, computed the same way for sizing and for carving.
 struct Layout {
-    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, units, wgt, act, out, partial, total;
+    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, go, units, wgt, act, out, partial, total;
     bool has_partial;
     uint32_t max_units;
 };
@@ -89,6 +89,7 @@ Layout make_layout(const moe_config &c) {
     L.blockoff = take((nblocks ? nblocks : 1) * 2 * E * 4);
     L.cls = take(N ? N : 1);
     L.done = take(A ? A : 1);           // completion flag per sorted row (moe_combine_complete)
+    L.go = take(((size_t)L.max_units + 1) * 4);   // gate words of an enqueued launch sequence
     L.units = take((size_t)L.max_units * sizeof(moe_unit));
     L.wgt = take(((E + 15) / 16 * 16) * (size_t)c.H * 2);
     L.act = take(A * (size_t)c.F * es);
@@ -116,8 +117,10 @@ struct moe_ctx {
     std::vector<uint8_t> executed;             // per unit
     std::vector<uint32_t> unmarked;            // executed units whose rows are not yet flagged on the device
     bool done_valid;                           // the device flags of this layer-batch have been cleared
+    bool pending;                              // an enqueued launch sequence has not been collected yet
+    std::vector<std::vector<uint32_t>> plan;   // the units of each launch of that sequence
     std::vector<int32_t> cnt;
-    int32_t *pinned;  // 2E counts, unit count, sequence word: pinned host memory mapped into the device
+    int32_t *pinned;  // 2E counts, unit count, sequence word, stop word, completed-launch count: pinned host memory mapped into the device
                       // (allocated at first route); the permutation kernels write it directly
     int32_t *pinned_dev;   // the device's address of the same memory
     int32_t seq;           // sequence number of the last report asked for
@@ -222,6 +225,7 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->N = 0;
     c->next_unit = c->n_units = c->n_ls_units = c->n_done = c->n_ls_done = 0;
     c->done_valid = false;
+    c->pending = false;
     c->pinned = nullptr;
     c->pinned_dev = nullptr;
     c->seq = 0;
@@ -244,6 +248,7 @@ int32_t moe_destroy(moe_ctx *ctx) {
 int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weights *w, const float *logit_bias,
                   void *stream) {
     if (!ctx) return fail(MOE_E_ARG, "moe_route: null context");
+    if (ctx->pending) return fail(MOE_E_STATE, "moe_route: an enqueued launch sequence is pending; call moe_expert_collect first");
     if (n_tokens < 0 || n_tokens > ctx->cfg.max_tokens)
         return fail(MOE_E_ARG, "moe_route: n_tokens %d outside 0..%d", n_tokens, ctx->cfg.max_tokens);
     if (!w || !w->Wg || !w->W1 || !w->W3 || !w->W2) return fail(MOE_E_ARG, "moe_route: null weight pointer");
@@ -253,7 +258,7 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     if (w->layout == MOE_W_MXFP4 && (!w->S1 || !w->S3 || !w->S2)) return fail(MOE_E_ARG, "moe_route: 4-bit weights need the scale pointers S1, S3, S2");
     if (n_tokens > 0 && !x) return fail(MOE_E_ARG, "moe_route: null x");
     if (!ctx->pinned) {
-        const size_t words = 2 * (size_t)ctx->cfg.E + 2;
+        const size_t words = 2 * (size_t)ctx->cfg.E + 4;   // counts, unit count, sequence word, stop word, completed launches
         hipError_t e = hipHostMalloc((void **)&ctx->pinned, words * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { ctx->pinned = nullptr; return hip_fail(e, "moe_route: hipHostMalloc"); }
         e = hipHostGetDevicePointer((void **)&ctx->pinned_dev, ctx->pinned, 0);
@@ -363,11 +368,12 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
 }
 
 // Launches the expert kernels for the listed units (already validated: in range, distinct, not
-// yet executed) and books them as executed.
-static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
-                             hipStream_t stream, const char *who) {
+// yet executed); go: gate word of the launch on the device, or nullptr.
+static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
+                                const int32_t *go, hipStream_t stream, const char *who) {
     if (ids.empty()) return MOE_OK;
     qmoe::ExpertArgs a{};
+    a.go = go;
     a.x = x; a.W1 = w->W1; a.W3 = w->W3; a.W2 = w->W2;
     a.perm = at<int32_t>(ctx, ctx->lay.perm);
     a.units = at<moe_unit>(ctx, ctx->lay.units);
@@ -451,19 +457,31 @@ static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, 
         }
     }
     if (e != hipSuccess) return hip_fail(e, who);
+    return MOE_OK;
+}
+
+// Books units as executed and moves the cursor to the first unit that has not run.
+static void book_units(moe_ctx *ctx, const std::vector<uint32_t> &ids) {
     for (uint32_t i : ids) {
         ctx->executed[i] = 1;
         ctx->n_done += 1;
-        ctx->n_ls_done += un[i].cls == 0;
+        ctx->n_ls_done += ctx->units[i].cls == 0;
         ctx->unmarked.push_back(i);
     }
     while (ctx->next_unit < ctx->n_units && ctx->executed[ctx->next_unit]) ++ctx->next_unit;
-    return MOE_OK;
+}
+
+static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
+                             hipStream_t stream, const char *who) {
+    const int32_t rc = launch_unit_list(ctx, x, w, ids, nullptr, stream, who);
+    if (rc == MOE_OK) book_units(ctx, ids);
+    return rc;
 }
 
 static int32_t check_run_args(moe_ctx *ctx, const void *x, const moe_weights *w, const char *who) {
     if (!ctx) return fail(MOE_E_ARG, "%s: null context", who);
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "%s: call moe_permute first", who);
+    if (ctx->pending) return fail(MOE_E_STATE, "%s: an enqueued launch sequence is pending; call moe_expert_collect first", who);
     if (!w || (ctx->N > 0 && !x)) return fail(MOE_E_ARG, "%s: null x or weights", who);
     if (x != ctx->x || w->W1 != ctx->w.W1 || w->W3 != ctx->w.W3 || w->W2 != ctx->w.W2 || w->layout != ctx->w.layout ||
         w->S1 != ctx->w.S1 || w->S3 != ctx->w.S3 || w->S2 != ctx->w.S2)
@@ -507,9 +525,70 @@ int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, 
     return ctx->n_done == ctx->n_units ? MOE_DONE : MOE_OK;
 }
 
+int32_t moe_expert_enqueue(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t units_per_launch, void *stream) {
+    int32_t rc = check_run_args(ctx, x, w, "moe_expert_enqueue");
+    if (rc != MOE_OK) return rc;
+    if (units_per_launch == 0) return fail(MOE_E_ARG, "moe_expert_enqueue: units_per_launch must be at least 1");
+    hipStream_t s = (hipStream_t)stream;
+    ctx->plan.clear();
+    for (uint32_t u = ctx->next_unit; u < ctx->n_units; ++u) {
+        if (ctx->executed[u]) continue;
+        if (ctx->plan.empty() || ctx->plan.back().size() >= units_per_launch) ctx->plan.emplace_back();
+        ctx->plan.back().push_back(u);
+    }
+    if (ctx->plan.empty()) return MOE_DONE;
+    const int E = ctx->cfg.E;
+    int32_t *stop = ctx->pinned + 2 * E + 2, *completed = ctx->pinned + 2 * E + 3;
+    *stop = 0;
+    *completed = 0;
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+    const int32_t *stop_dev = ctx->pinned_dev + 2 * E + 2;
+    int32_t *completed_dev = ctx->pinned_dev + 2 * E + 3;
+    int32_t *go = at<int32_t>(ctx, ctx->lay.go);
+    const int n = (int)ctx->plan.size();
+    ctx->pending = true;     // from here on the stream holds launches that read this context's state
+    for (int g = 0; g <= n; ++g) {
+        hipError_t e = qmoe::launch_gate(stop_dev, completed_dev, go, g, n, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_expert_enqueue: gate");
+        if (g == n) break;
+        rc = launch_unit_list(ctx, x, w, ctx->plan[g], go + g, s, "moe_expert_enqueue: launch");
+        if (rc != MOE_OK) return rc;
+    }
+    return MOE_OK;
+}
+
+int32_t moe_expert_stop(moe_ctx *ctx) {
+    if (!ctx) return fail(MOE_E_ARG, "moe_expert_stop: null context");
+    if (!ctx->pinned) return fail(MOE_E_STATE, "moe_expert_stop: nothing has been routed on this context");
+    __atomic_store_n(ctx->pinned + 2 * ctx->cfg.E + 2, 1, __ATOMIC_SEQ_CST);
+    return MOE_OK;
+}
+
+int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream) {
+    if (!ctx) return fail(MOE_E_ARG, "moe_expert_collect: null context");
+    if (!cursor) return fail(MOE_E_ARG, "moe_expert_collect: null cursor");
+    if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_expert_collect: call moe_permute first");
+    if (ctx->pending) {
+        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, "moe_expert_collect: waiting for the stream");
+        std::atomic_thread_fence(std::memory_order_acquire);
+        const int32_t completed = *(volatile int32_t *)(ctx->pinned + 2 * ctx->cfg.E + 3);
+        if (completed < 0 || (size_t)completed > ctx->plan.size())
+            return fail(MOE_E_HIP, "moe_expert_collect: the device reports %d completed launches of %zu", completed, ctx->plan.size());
+        for (int32_t g = 0; g < completed; ++g) book_units(ctx, ctx->plan[g]);
+        ctx->plan.clear();
+        ctx->pending = false;
+        __atomic_store_n(ctx->pinned + 2 * ctx->cfg.E + 2, 0, __ATOMIC_SEQ_CST);
+    }
+    cursor->next_unit = ctx->next_unit;
+    cursor->n_units = ctx->n_units;
+    return ctx->n_done == ctx->n_units ? MOE_DONE : MOE_OK;
+}
+
 int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
     if (!ctx) return fail(MOE_E_ARG, "moe_combine: null context");
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_combine: call moe_permute first");
+    if (ctx->pending) return fail(MOE_E_STATE, "moe_combine: an enqueued launch sequence is pending; call moe_expert_collect first");
     if (class_mask < 1 || class_mask > 3) return fail(MOE_E_ARG, "moe_combine: class_mask must be 1, 2 or 3");
     if (ctx->N > 0 && !y) return fail(MOE_E_ARG, "moe_combine: null y");
     const uint32_t ls_left = ctx->n_ls_units - ctx->n_ls_done;
@@ -534,6 +613,7 @@ int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
 int32_t moe_combine_complete(moe_ctx *ctx, void *y, uint8_t *complete, void *stream) {
     if (!ctx) return fail(MOE_E_ARG, "moe_combine_complete: null context");
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_combine_complete: call moe_permute first");
+    if (ctx->pending) return fail(MOE_E_STATE, "moe_combine_complete: an enqueued launch sequence is pending; call moe_expert_collect first");
     if (ctx->N > 0 && !y) return fail(MOE_E_ARG, "moe_combine_complete: null y");
     if (ctx->N == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)stream;

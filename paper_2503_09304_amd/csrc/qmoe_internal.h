@@ -89,6 +89,7 @@ struct ExpertArgs {
     int ksplit;                 // 1 or 4 (down projection; fixed per context)
     float *partial;             // [4][A][H] fp32 partial planes of the K-split down projection, or nullptr
     long plane;                 // elements per plane
+    const int32_t *go;          // gate word of this launch on the device, or nullptr (see launch_gate)
 };
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
 
@@ -110,6 +111,10 @@ struct CombineArgs {
     int N, H, k, dtype, class_mask;
 };
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
+// Gate between the launches of an enqueued sequence (moe_expert_enqueue): one thread.  If commit != 0
+// and go[g-1] is set, launch g-1 ran in full: *completed (host memory) = g.  Then, if g < n_launches,
+// go[g] = (g == 0 || go[g-1]) && *stop == 0: once a gate closes, every later one stays closed.
+hipError_t launch_gate(const int32_t *stop_host, int32_t *completed_host, int32_t *go, int g, int n_launches, hipStream_t s);
 // Completion flags per sorted row (used by moe_combine_complete): clear all, set the rows of segments.
 hipError_t launch_clear_done(uint8_t *done, long n, hipStream_t s);
 hipError_t launch_mark_done(const Seg *segs, int n, uint8_t *done, hipStream_t s);
