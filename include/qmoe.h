@@ -214,7 +214,8 @@ int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, 
  * (a plain host store; may be called from another thread than the one that enqueued).  Work of other
  * contexts may be enqueued on the stream at any time; it runs behind whatever the sequence still
  * executes (at most the launch in progress plus the empty shells of the rest).
- * moe_expert_collect waits for the stream, reads how many launches ran in full, books their units as
+ * moe_expert_collect waits for the stream (unless the device has already reported the whole sequence
+ * complete), reads how many launches ran in full, books their units as
  * executed, clears the stop word and returns the cursor in *cursor ([host]); MOE_DONE if every unit
  * has run, MOE_OK otherwise (then carry on with moe_expert_enqueue or moe_expert_run).  A launch
  * either ran completely or not at all, and its arithmetic is that of moe_expert_run, bit for bit.

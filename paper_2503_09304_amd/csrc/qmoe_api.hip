@@ -569,10 +569,15 @@ int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream) {
     if (!cursor) return fail(MOE_E_ARG, "moe_expert_collect: null cursor");
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_expert_collect: call moe_permute first");
     if (ctx->pending) {
-        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
-        if (e != hipSuccess) return hip_fail(e, "moe_expert_collect: waiting for the stream");
+        // If the last gate has already reported every launch complete there is nothing to wait for;
+        // otherwise the count is final only once the stream has drained.
+        volatile int32_t *word = ctx->pinned + 2 * ctx->cfg.E + 3;
+        if ((size_t)*word != ctx->plan.size()) {
+            hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+            if (e != hipSuccess) return hip_fail(e, "moe_expert_collect: waiting for the stream");
+        }
         std::atomic_thread_fence(std::memory_order_acquire);
-        const int32_t completed = *(volatile int32_t *)(ctx->pinned + 2 * ctx->cfg.E + 3);
+        const int32_t completed = *word;
         if (completed < 0 || (size_t)completed > ctx->plan.size())
             return fail(MOE_E_HIP, "moe_expert_collect: the device reports %d completed launches of %zu", completed, ctx->plan.size());
         for (int32_t g = 0; g < completed; ++g) book_units(ctx, ctx->plan[g]);

@@ -13,11 +13,14 @@ jobs through the stack and yields each job's first token; a decode iteration run
 job.  Hidden states are rows of a fixed seeded bank, selected by (job, token index).
 
 Two policies share all of that code:
-  * preemptive=True: jobs keep their class; while a batch of BE jobs only is executing, the loop asks
-    the scheduler at every expert-chunk boundary (bounded look-ahead of moe_expert_run calls) whether
-    an LS prompt waits; if so it parks the batch where it is (its context and cursor stay on the
-    device), runs the batch the scheduler hands out next (the LS prefill) through all layers,
-    reports its tokens, and resumes the parked batch from its cursor.
+  * preemptive=True: jobs keep their class; while a batch of BE jobs only is executing, the loop keeps
+    asking the scheduler whether an LS prompt waits; if so it parks the batch at the next expert-chunk
+    boundary (its context and cursor stay on the device), runs the batch the scheduler hands out
+    next (the LS prefill) through all layers, reports its tokens, and resumes the parked batch from
+    its cursor.  device_stop=True: the expert work of a prefill layer is on the stream as gated
+    launches (moe_expert_enqueue) and parking is a host store of the stop word; decode layers (a
+    handful of units each) and device_stop=False feed the work moe_expert_run by moe_expert_run with
+    a bounded look-ahead.
   * preemptive=False: the priority-oblivious run-to-completion baseline.  Every job is submitted as
     BE, so the algorithm degenerates to "decode before prefill": a batch, once prefilled, decodes
     until all its jobs are done before the next prompts are taken; control returns to the scheduler
@@ -85,9 +88,10 @@ class _Slot:
 class Engine:
     def __init__(self, weights: q.MoeWeights, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
                  max_prompt: int, preemptive: bool, units_per_call: int = 4, lookahead: int = 1, chunk_rows: int = 256,
-                 bank_rows: int = 4096, seed: int = 1, digest: bool = False, device="cuda:0"):
+                 bank_rows: int = 4096, seed: int = 1, digest: bool = False, device_stop: bool = True, device="cuda:0"):
         self.w, self.layers, self.batch_size, self.max_prompt = weights, layers, batch_size, max_prompt
         self.preemptive, self.units_per_call, self.lookahead = preemptive, units_per_call, lookahead
+        self.device_stop = device_stop
         self.device = device
         g = torch.Generator(device=device)
         g.manual_seed(seed)
@@ -154,6 +158,27 @@ class Engine:
                 self.ls_rows_expected += ctx.cfg.k * int(slot.prio[:n].sum().item())
             if not preemptible:
                 ctx.expert_run(x, self.w)
+            elif self.device_stop and stage == q.SCHED_PREFILL:
+                # the whole layer goes on the stream as gated launches; the loop watches for an LS
+                # prompt meanwhile and closes the gates when one waits
+                rc = ctx.expert_enqueue(x, self.w, self.units_per_call)
+                while rc != q.MOE_DONE:
+                    ev = torch.cuda.Event()
+                    ev.record()
+                    while not ev.query():
+                        self._admit()
+                        if self.sched.preempt_wanted(0):
+                            ctx.expert_stop()
+                            while self.sched.preempt_wanted(0):
+                                self.trace.append(("preempt", tuple(jobs)))
+                                self.preemptions += 1
+                                got = self._next_batch()
+                                self._iteration(*got, level=1)     # runs behind the launch in progress
+                                self._admit()
+                            break
+                    rc = ctx.expert_collect()
+                    if rc != q.MOE_DONE:
+                        rc = ctx.expert_enqueue(x, self.w, self.units_per_call)
             else:
                 pending, done = [], False
                 while not done:

@@ -57,21 +57,22 @@ def engine(weights, preemptive, **kw):
 def test_stream_completes_and_is_bit_identical_across_policies(weights):
     d = wl.make_jobs(40, rate_per_s=2500.0, p_ls=0.25, seed=7, max_prompt=MAX_PROMPT, max_out=6, min_prompt=8, min_out=2)
     results = {}
-    for pre in (False, True):
+    for pre in (False, True, "host-fed"):
         jobs = jobs_from(d)
-        eng = engine(weights, pre)
+        eng = engine(weights, bool(pre), device_stop=pre is True)
         st = eng.run(jobs)
         print(st)
         assert all(j.tokens == j.out_len and j.ttft_s >= 0 and j.done_s >= j.ttft_s for j in jobs)
         assert st["prefill_iterations"] + st["decode_iterations"] == replay(eng.trace, BATCH)
         assert eng.sched.running() == 0 and all(eng.sched.queue_len(i) == 0 for i in range(4))
         assert int(eng.ls_rows_seen.item()) == eng.ls_rows_expected      # the layers saw the batch's priority flags
-        assert (eng.ls_rows_expected > 0) == pre
+        assert (eng.ls_rows_expected > 0) == bool(pre)
         results[pre] = (st, eng.digest.cpu().numpy().copy())
     assert results[False][0]["preemptions"] == 0
-    assert results[True][0]["preemptions"] > 0
+    assert results[True][0]["preemptions"] > 0 and results["host-fed"][0]["preemptions"] > 0
     # batch composition, priority order and preemption change when a row is computed, never its value
     assert np.array_equal(results[False][1], results[True][1])
+    assert np.array_equal(results[False][1], results["host-fed"][1])
     assert np.any(results[True][1] != 0)
 
 
