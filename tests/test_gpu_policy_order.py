@@ -125,3 +125,38 @@ def test_bad_unit_lists_run_nothing():
     g.combine()
     torch.cuda.synchronize()
     assert torch.equal(g.y.view(torch.int16), ref.y.view(torch.int16))
+
+
+def test_example_policies():
+    from paper_2503_09304_amd import policies
+    cfg = wl.LayerConfig("p6", dtype="bf16", seed=935, E=8, k=2, H=128, F=256, N=400, n_ls=90, chunk_rows=32,
+                         bias_kind="zipf", bias_arg=1.1)
+    inp = wl.make_inputs(cfg)
+    ref = GpuLayer(inp).full()
+    it = torch.int16
+    # busiest expert first: same bits as the list order
+    g = GpuLayer(inp, ref.dw)
+    g.route_permute()
+    units = g.ctx.units()
+    order = policies.busiest_expert_first(units)
+    assert sorted(order) == policies.list_order(units)
+    assert [units[i][1] for i in order] == sorted(u[1] for u in units)         # LS chunks still first
+    assert g.ctx.expert_run_units(g.x, g.dw.struct, order) == q.MOE_DONE
+    g.combine()
+    torch.cuda.synchronize()
+    assert torch.equal(g.y.view(it), ref.y.view(it))
+    # hold one expert back: exactly the tokens that did not choose it are complete
+    g = GpuLayer(inp, ref.dw)
+    g.route_permute()
+    held = 2
+    now, later = policies.without_experts(units, [held])
+    g.ctx.expert_run_units(g.x, g.dw.struct, now)
+    comp = torch.zeros(cfg.N, dtype=torch.uint8, device=DEV)
+    g.ctx.combine_complete(g.y, comp)
+    torch.cuda.synchronize()
+    idx = to_host(g.ctx.get("topk_idx"))
+    assert np.array_equal(comp.cpu().numpy().astype(bool), ~(idx == held).any(axis=1))
+    assert g.ctx.expert_run_units(g.x, g.dw.struct, later) == q.MOE_DONE
+    g.combine()
+    torch.cuda.synchronize()
+    assert torch.equal(g.y.view(it), ref.y.view(it))
