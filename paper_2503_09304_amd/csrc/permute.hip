@@ -99,17 +99,42 @@ __global__ __launch_bounds__(1024) void perm_scan(int32_t *__restrict__ blockcnt
     __shared__ int32_t ustart[2 * kMaxExperts];
     __shared__ int32_t tmp[2 * kMaxExperts];
     const int nb = 2 * E, tid = threadIdx.x;
-    for (int b = tid; b < nb; b += blockDim.x) {
+    // Per bucket, the exclusive prefix over the blocks.  The 1024 threads cut the blocks into
+    // `slices` ranges per bucket (thread = (slice, bucket)): sums of the ranges, their prefix through
+    // LDS, then each thread rewrites its range; the loads of a range do not depend on one another.
+    __shared__ int32_t part[1024];
+    const int slices = blockDim.x / nb > 0 ? blockDim.x / nb : 1;
+    const int per = (nblocks + slices - 1) / slices;
+    for (int b0 = 0; b0 < nb; b0 += blockDim.x) {            // one pass unless there are more buckets than threads
+        const int sl = slices > 1 ? tid / nb : 0;
+        const int b = b0 + (slices > 1 ? tid - sl * nb : tid);
+        const bool active = b < nb && sl < slices;
+        const int blk0 = sl * per, blk1 = min(nblocks, blk0 + per);
+        int sum = 0;
+        if (active)
+            for (int blk = blk0; blk < blk1; ++blk) sum += blockcnt[(long)blk * nb + b];
+        if (active && slices > 1) part[sl * nb + (b - b0)] = sum;
+        __syncthreads();
         int run = 0;
-        for (int blk = 0; blk < nblocks; ++blk) {
-            const int c = blockcnt[(long)blk * nb + b];
-            blockcnt[(long)blk * nb + b] = run;
-            run += c;
+        if (active && slices > 1) {
+            int total = 0;
+            for (int q = 0; q < slices; ++q) {
+                const int v = part[q * nb + (b - b0)];
+                if (q < sl) run += v;
+                total += v;
+            }
+            sum = total;
         }
-        tot[b] = run;
-        boff[b] = run;
+        if (active) {
+            for (int blk = blk0; blk < blk1; ++blk) {
+                const int c = blockcnt[(long)blk * nb + b];
+                blockcnt[(long)blk * nb + b] = run;
+                run += c;
+            }
+            if (sl == 0) { tot[b] = sum; boff[b] = sum; }
+        }
+        __syncthreads();
     }
-    __syncthreads();
     const int total = block_excl_scan(boff, tmp, nb);
     for (int b = tid; b < nb; b += blockDim.x) {
         cnt[b] = tot[b];
