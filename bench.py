@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2019327730, "cfg4": 1913119136, "cfg3_be": 3650022154, "cfg5": 2704743648,
-                          "cfg4_mxfp4": 516125213, "cfg3_be_mxfp4": 1542261805}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2019684508, "cfg4": 1913245597, "cfg3_be": 3651180041, "cfg5": 2694489140,
+                          "cfg4_mxfp4": 516002341, "cfg3_be_mxfp4": 1539863417}
 
 
 def log(*a):
