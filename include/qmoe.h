@@ -178,8 +178,9 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
  * unit.  Waits for the counts (the engine's report to the scheduler after the router stage,
  * Sec. 3.2): the kernel stores them into pinned host memory as soon as it knows them and the call
  * polls for that, so it returns while the rest of the permutation may still be running; whatever is
- * enqueued on the stream afterwards is ordered behind it.  Returns the cursor {0, n_units} in
- * *cursor ([host]). */
+ * enqueued on the stream afterwards is ordered behind it.  If the report does not arrive within
+ * 200 ms (environment variable QMOE_REPORT_SPIN_MS at moe_create, 0 = never poll) the call waits for
+ * the stream instead.  Returns the cursor {0, n_units} in *cursor ([host]). */
 int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void *stream);
 
 /* Expert work, resumable (Sec. 3.1 "Top-k expert selection"; Introduction, contribution 3).

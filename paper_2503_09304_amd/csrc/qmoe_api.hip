@@ -5,6 +5,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <algorithm>
 #include <atomic>
 #include <chrono>
@@ -124,6 +125,7 @@ struct moe_ctx {
                       // (allocated at first route); the permutation kernels write it directly
     int32_t *pinned_dev;   // the device's address of the same memory
     int32_t seq;           // sequence number of the last report asked for
+    int spin_ms;           // how long moe_permute polls for the report before it waits for the stream
     const void *x;
     moe_weights w;
     qmoe::Profiler prof;
@@ -229,6 +231,11 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->pinned = nullptr;
     c->pinned_dev = nullptr;
     c->seq = 0;
+    c->spin_ms = kReportSpinMs;
+    if (const char *v = getenv("QMOE_REPORT_SPIN_MS")) {      // for tests of the fall-back: 0 = do not poll at all
+        const long ms = strtol(v, nullptr, 10);
+        if (ms >= 0 && ms <= 60000) c->spin_ms = (int)ms;
+    }
     c->prof_on = false;
     c->x = nullptr;
     c->w = moe_weights{};
@@ -327,10 +334,10 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
         volatile int32_t *word = ctx->pinned + 2 * E + 1;
         const auto t0 = std::chrono::steady_clock::now();
         bool seen = false;
-        for (unsigned spins = 0;; ++spins) {
+        for (unsigned spins = 0; ctx->spin_ms > 0; ++spins) {
             if (*word == ctx->seq) { seen = true; break; }
             if ((spins & 1023u) == 1023u &&
-                std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(kReportSpinMs)) break;
+                std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(ctx->spin_ms)) break;
         }
         if (!seen) {
             e = hipStreamSynchronize(s);

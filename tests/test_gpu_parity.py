@@ -304,3 +304,18 @@ def test_context_reuse_with_a_smaller_batch_and_run_to_run_identity():
     g2.full()
     ref = GpuLayer(isml).full()
     assert torch.equal(bits(g2.y), bits(ref.y))
+
+
+def test_permute_falls_back_to_a_stream_wait_when_it_may_not_poll(monkeypatch):
+    """QMOE_REPORT_SPIN_MS=0 makes moe_permute skip the poll of the kernel's report and wait for the
+    stream: same cursor, same bits."""
+    cfg = wl.LayerConfig("s14", dtype="bf16", seed=923, E=8, k=2, H=128, F=256, N=500, n_ls=100, chunk_rows=64)
+    inp = wl.make_inputs(cfg)
+    ref = GpuLayer(inp).full()
+    monkeypatch.setenv("QMOE_REPORT_SPIN_MS", "0")
+    g = GpuLayer(inp, ref.dw)                      # the variable is read when the context is created
+    monkeypatch.delenv("QMOE_REPORT_SPIN_MS")
+    for _ in range(3):
+        g.full()
+        assert g.ctx.cursor.n_units == ref.ctx.cursor.n_units
+        assert torch.equal(bits(g.y), bits(ref.y))
