@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
@@ -298,7 +297,7 @@ def main() -> int:
 
     import paper_2503_09304_amd as q
     import workloads as wl
-    from gpu_util import DevWeights, GpuLayer
+    from paper_2503_09304_amd.layer import DevWeights, GpuLayer
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
@@ -311,7 +310,7 @@ def main() -> int:
     mx = args.weights == "mxfp4"
     ws = 0.5 + 1.0 / 32 if mx else es      # bytes per expert-weight element (4-bit code + its share of a scale byte)
     if mx:
-        from gpu_util import DevWeightsMX
+        from paper_2503_09304_amd.layer import DevWeightsMX
         w4 = wl.make_weights_mxfp4(cfg)
         inp = wl.make_inputs(cfg, weights={})
     else:
