@@ -131,6 +131,13 @@ def small_cases():
     yield "bf16_one_token", wl.LayerConfig("s11", **{**base, "N": 1, "n_ls": 1, "seed": 920})
     yield "bf16_many_experts", wl.LayerConfig("s12", dtype="bf16", seed=921, E=256, k=6, H=128, F=128, N=257,
                                               n_ls=64, chunk_rows=32)
+    # the limits of the configuration: top-32 routing, one row per unit, the smallest bf16 dimensions
+    yield "bf16_top32", wl.LayerConfig("s15", dtype="bf16", seed=924, E=64, k=32, H=128, F=128, N=40, n_ls=10,
+                                       chunk_rows=64)
+    yield "bf16_one_row_units", wl.LayerConfig("s16", dtype="bf16", seed=925, E=4, k=2, H=128, F=128, N=20, n_ls=5,
+                                               chunk_rows=1)
+    yield "bf16_min_dims", wl.LayerConfig("s17", dtype="bf16", seed=926, E=3, k=2, H=64, F=64, N=70, n_ls=20,
+                                          chunk_rows=16)
     # more row segments than fit the kernel arguments: the launch reads the device unit list instead
     yield "bf16_many_segments", wl.LayerConfig("s13", dtype="bf16", seed=922, E=64, k=8, H=128, F=128, N=16384,
                                                n_ls=4000, chunk_rows=256)
