@@ -16,16 +16,19 @@
 // Pipeline of one K-iteration (64 k), prefetch distance D: issue the global loads of the token
 // pieces and weight fragments for it+D (register rings of D+1 sets), run the MFMAs of iteration it,
 // write the token tile for it+1 into the other LDS stage, one barrier.  Vector loads complete in
-// issue order, so the waits leave about D iterations of weight loads (8 KB per wave each) in flight.  Loads are unconditional (row and iteration indices are
-// clamped instead) so that the wait counters stay exact.
+// issue order, so the waits leave about D iterations of weight loads (8 KB per wave each) in flight.
+// Loads are unconditional (row and iteration indices are clamped instead) so that the wait counters
+// stay exact.
 //
 // Down projection with K-split (a property of the context's configuration: weight-streaming shapes
 // have too few output tiles to fill the chip): K is cut into 4 contiguous quarters, each computed by
 // its own workgroup into a partial plane; a second kernel adds the planes in the fixed order
 // ((p0+p1)+p2)+p3.
 //
-// A launch works on row segments: a unit, or several row-adjacent units of one expert merged by the
-// host (the LS and BE part of an expert's queue), so that one pass over the weights serves them.
+// A launch works on row segments: the host joins the row-adjacent units of one expert in a call (the
+// LS and BE part of its queue, consecutive chunks) and cuts each such run into segments of at most 8
+// token tiles with equal tile counts, so that one pass over the weights serves them and workgroups
+// that share weight tiles keep the same pace.
 //
 // Determinism.  Each output element is one chain of MFMA accumulations over K in ascending order
 // (K-split: 4 chains added in a fixed order), the same for every row of the context: it depends on
