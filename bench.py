@@ -398,6 +398,28 @@ def main() -> int:
                  "down_algorithmic_bytes_per_step": int(dnb),
                  "down_achieved_GBps": round(dnb / (dn_ms / max(args.steps, 1) * 1e-3) / 1e9, 1) if dn_ms > 0 else None})
 
+    # ---- LS tokens first inside a mixed batch: run the LS units, combine the LS rows, then the rest
+    ls_first = None
+    n_ls_units = sum(1 for u in g.ctx.units() if u[1] == 0)
+    if 0 < n_ls_units < g.ctx.cursor.n_units:
+        t_ls, t_all = [], []
+        for _ in range(10):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g.route_permute()
+            g.run(n_ls_units)
+            g.combine(q.MOE_CLASS_LS)
+            e_ls = torch.cuda.Event(); e_ls.record()
+            g.run()
+            g.combine(q.MOE_CLASS_BE)
+            e_ls.synchronize()
+            t_ls.append(time.perf_counter() - t0)
+            torch.cuda.synchronize()
+            t_all.append(time.perf_counter() - t0)
+        ls_first = {"ls_rows_ready_ms": round(1e3 * float(np.median(t_ls)), 4), "whole_batch_ms": round(1e3 * float(np.median(t_all)), 4),
+                    "single_call_ms": round(ms_per_step, 4), "ls_units": n_ls_units, "units": int(g.ctx.cursor.n_units)}
+        log("LS-first inside the mixed batch:", json.dumps(ls_first))
+
     # ---- LS latency while a long BE batch is in flight (Mixtral weights)
     lat = None
     if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx:
@@ -444,6 +466,7 @@ def main() -> int:
         "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
         "stages_ms": stages,
         "roofline": roof,
+        "ls_first_in_mixed_batch": ls_first,
         "ls_latency_under_be_load": lat,
         "cpu_baseline": cpu,
     }
