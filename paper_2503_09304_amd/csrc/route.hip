@@ -9,7 +9,8 @@
 // add their partial tiles through LDS in wave order, so the summation order is fixed; the same
 // workgroup then selects the experts (fused, no second launch).
 // fp32: one wave per token, lanes stride the hidden dimension, butterfly reduction; separate top-k.
-// top-k: one wave per token; k rounds of a wave-wide arg-max over (logit desc, index asc).
+// top-k: one wave per token.  bf16: every lane ranks its experts against the whole row of logits in
+// LDS (order: logit desc, index asc).  fp32: k rounds of a wave-wide arg-max over the same order.
 #include <hip/hip_runtime.h>
 
 #include "qmoe_internal.h"
@@ -67,6 +68,67 @@ __device__ __forceinline__ void wave_topk(const float (&v)[kSlots], int l, int E
     }
 }
 
+// Top-k by ranking, for logits that sit in LDS: lane l counts, for each of its experts l, l+64, ...,
+// how many experts precede it in the order (logit descending, index ascending); an expert of rank
+// < k is the token's slot `rank`.  No chain of dependent shuffles: the E reads of the row are
+// broadcasts.  The selected logits go through `slot_v` / `slot_e` (k entries of LDS, private to the
+// wave) so that lane j holds slot j, and the weights are the same softmax, summed in the same
+// butterfly order, as wave_topk computes.
+__device__ __forceinline__ void wave_topk_rank(const float *__restrict__ row, float *__restrict__ slot_v,
+                                               int32_t *__restrict__ slot_e, int l, int E, int k,
+                                               int32_t *__restrict__ idx_out, float *__restrict__ w_out) {
+    float mine[kSlots];
+    int rank[kSlots];
+#pragma unroll
+    for (int c = 0; c < kSlots; ++c) {
+        const int e = l + 64 * c;
+        mine[c] = e < E ? row[e] : 0.f;
+        rank[c] = 0;
+    }
+    const int nslots = (E + 63) >> 6;
+    const int E8 = E & ~7;
+    for (int o0 = 0; o0 < E8; o0 += 8) {                 // 8 broadcast reads in flight at a time
+        float ov[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ov[i] = row[o0 + i];
+#pragma unroll
+        for (int c = 0; c < kSlots; ++c) {
+            if (c < nslots) {
+                const int e = l + 64 * c;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) rank[c] += (ov[i] > mine[c] || (ov[i] == mine[c] && o0 + i < e)) ? 1 : 0;
+            }
+        }
+    }
+    for (int o = E8; o < E; ++o) {
+        const float ov = row[o];
+#pragma unroll
+        for (int c = 0; c < kSlots; ++c) {
+            const int e = l + 64 * c;
+            if (c < nslots) rank[c] += (ov > mine[c] || (ov == mine[c] && o < e)) ? 1 : 0;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < kSlots; ++c) {
+        const int e = l + 64 * c;
+        if (e < E && rank[c] < k) { slot_v[rank[c]] = mine[c]; slot_e[rank[c]] = e; }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);      // this wave's LDS writes have landed
+    __builtin_amdgcn_wave_barrier();
+    const float my_v = l < k ? slot_v[l] : 0.f;
+    const int my_e = l < k ? slot_e[l] : 0;
+    const float top = __shfl(my_v, 0, 64);
+    const float p = l < k ? expf(my_v - top) : 0.f;
+    float s = p;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (l < k) {
+        idx_out[l] = my_e;
+        w_out[l] = p / s;
+    }
+    __builtin_amdgcn_wave_barrier();         // slot_v / slot_e are reused for the wave's next token
+}
+
 // Gate GEMM and top-k of 16 tokens per workgroup.  NB = number of 16-expert blocks held in
 // registers (E16 <= 16*NB).  The 8 waves split the hidden dimension into 8 contiguous ranges (loads
 // issued 8 k-steps at a time), add their partial tiles through LDS in wave order, and then each
@@ -78,6 +140,8 @@ __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict
                                                       int E, int nb, int k) {
     __shared__ float red[7][NB][4][64];
     __shared__ float lt[16][NB * 16 + 1];
+    __shared__ float slot_v[8][kMaxTopK];
+    __shared__ int32_t slot_e[8][kMaxTopK];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int t16 = l & 15, q = l >> 4;
     int tok = blockIdx.x * 16 + t16;
@@ -141,15 +205,7 @@ __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict
     for (int h = 0; h < 2; ++h) {
         const int tl = w * 2 + h;
         const int t = blockIdx.x * 16 + tl;
-        if (t < N) {
-            float v[kSlots];
-#pragma unroll
-            for (int c = 0; c < kSlots; ++c) {
-                const int e = l + 64 * c;
-                v[c] = e < E ? lt[tl][e] : -INFINITY;
-            }
-            wave_topk(v, l, E, k, topk_idx + (long)t * k, topk_w + (long)t * k);
-        }
+        if (t < N) wave_topk_rank(lt[tl], slot_v[w], slot_e[w], l, E, k, topk_idx + (long)t * k, topk_w + (long)t * k);
     }
 }
 
