@@ -444,7 +444,7 @@ def main() -> int:
         log(f"oracle: {ns} tokens in {t_cpu:.1f}s on {oracle.threads()} threads")
 
     out = {
-        "metric": "MoE-layer tokens/s",
+        "metric": "MoE-layer tokens/s + % MFMA/HBM roofline (Mixtral shape); LS latency under BE load",
         "value": round(tokens_per_s, 1),
         "unit": "tokens/s",
         "n_gpus": 1,
