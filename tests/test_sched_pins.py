@@ -203,3 +203,20 @@ def test_random_trace_invariants(seed):
     assert finished == next_id and not s.cls and not s.running           # every job completes once
     for key in order:
         assert served[key] == order[key]                                  # each queue is FCFS
+
+
+def test_synthetic_request_stream_recipe():
+    import workloads as wl
+    a = wl.make_jobs(4000, rate_per_s=80.0, p_ls=0.2, seed=5, max_prompt=512, max_out=32)
+    b = wl.make_jobs(4000, rate_per_s=80.0, p_ls=0.2, seed=5, max_prompt=512, max_out=32)
+    for k in a:
+        assert np.array_equal(a[k], b[k])                               # seeded
+    assert np.all(np.diff(a["arrival_s"]) > 0)
+    assert abs(4000 / a["arrival_s"][-1] - 80.0) < 5.0                   # Poisson arrivals at the stated rate
+    gaps = np.diff(a["arrival_s"])
+    assert abs(gaps.std() / gaps.mean() - 1.0) < 0.1                     # exponential gaps: cv = 1
+    assert abs(a["is_ls"].mean() - 0.2) < 0.03                           # a fifth of the prompts marked LS
+    assert a["prompt_len"].min() >= 16 and a["prompt_len"].max() <= 512
+    assert a["out_len"].min() >= 4 and a["out_len"].max() <= 32
+    c = wl.make_jobs(4000, rate_per_s=80.0, p_ls=0.2, seed=6)
+    assert not np.array_equal(a["prompt_len"], c["prompt_len"])
