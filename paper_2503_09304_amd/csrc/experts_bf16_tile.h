@@ -92,6 +92,10 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
                                             const long plane, char *lds) {
     constexpr int ROWS = T * 32;
     constexpr int STAGE = ROWS * 128;      // bytes of one LDS stage: 64 bf16 per row
+    // The 7- and 8-tile variants are MFMA-bound: they keep three token-tile stages, write tile it+2
+    // during iteration it, and so may read the first fragments of tile it+1 before the iteration's
+    // barrier; the LDS latency after the barrier disappears from the MFMA stream.
+    constexpr bool P3 = T >= 7;
     constexpr int CPW = GATEUP ? 32 : 64;  // output columns per wave
     const int rows = un.rows;
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
@@ -258,13 +262,14 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
             });
         });
     };
-    auto mfma_tile = [&](int stage, auto setc) {
+    auto mfma_tile = [&](int stage, int next_stage, auto setc) {
         constexpr int S = MX ? 0 : decltype(setc)::value;
         if constexpr (MX) dequant_b(setc);
-        read_af(stage, std::integral_constant<int, 0>{});
+        if constexpr (!P3) read_af(stage, std::integral_constant<int, 0>{});
         static_for<STEPS>([&](auto hsc) {
             constexpr int hs = decltype(hsc)::value, ks = hs / NH, h = hs % NH;
             if constexpr (hs + 1 < STEPS) read_af(stage, std::integral_constant<int, hs + 1>{});
+            else if constexpr (P3) read_af(next_stage, std::integral_constant<int, 0>{});
             static_for<HT>([&](auto tc) {
                 constexpr int t = h * HT + decltype(tc)::value;
                 const bf16x8 a = af[(hs & 1) * HT + decltype(tc)::value];
@@ -279,11 +284,11 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     // instead of in a burst), the T LDS writes of the next token tile over the last slots.
     auto pipeline = [&]() {
         constexpr int NS = 4 * T, NV = T + 8, HALF = NS / 2;
-        __builtin_amdgcn_sched_group_barrier(0x100, HT, 0);
+        if constexpr (!P3) __builtin_amdgcn_sched_group_barrier(0x100, HT, 0);
         static_for<NS>([&](auto sc) {
             constexpr int sl = decltype(sc)::value;
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            if constexpr (sl < NS - HT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if constexpr (P3 || sl < NS - HT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             if constexpr (sl < HALF) {
                 constexpr int vm = NV / HALF + (sl < NV % HALF ? 1 : 0);
                 if constexpr (vm > 0) __builtin_amdgcn_sched_group_barrier(0x020, vm, 0);
@@ -298,10 +303,18 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     auto body = [&](int it, auto ic) {
         constexpr int i = decltype(ic)::value;
         __builtin_amdgcn_sched_barrier(0);
-        load_a(it + DA, std::integral_constant<int, (i + DA) % NA>{});
-        load_b(it + D, std::integral_constant<int, (i + D) % NB>{});
-        mfma_tile(it & 1, std::integral_constant<int, i % NB>{});
-        store_a((it + 1) & 1, std::integral_constant<int, (i + 1) % NA>{});
+        if constexpr (P3) {
+            static_assert(!P3 || (NA == 1 && U % 3 == 0), "three stages: one token register set, loop unrolled by a multiple of 3");
+            load_a(it + 2, std::integral_constant<int, 0>{});
+            load_b(it + D, std::integral_constant<int, (i + D) % NB>{});
+            mfma_tile(i % 3, (i + 1) % 3, std::integral_constant<int, i % NB>{});
+            store_a((i + 2) % 3, std::integral_constant<int, 0>{});
+        } else {
+            load_a(it + DA, std::integral_constant<int, (i + DA) % NA>{});
+            load_b(it + D, std::integral_constant<int, (i + D) % NB>{});
+            mfma_tile(it & 1, 0, std::integral_constant<int, i % NB>{});
+            store_a((it + 1) & 1, std::integral_constant<int, (i + 1) % NA>{});
+        }
         pipeline();
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -311,13 +324,18 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     load_a(0, std::integral_constant<int, 0>{});
     load_b(0, std::integral_constant<int, 0>{});
     store_a(0, std::integral_constant<int, 0>{});
+    if constexpr (P3) {                      // three stages: tile 1 goes into stage 1 as well
+        load_a(1, std::integral_constant<int, 0>{});
+        store_a(1, std::integral_constant<int, 0>{});
+    }
     static_for<D - 1>([&](auto ic) {
         constexpr int j = decltype(ic)::value + 1;
-        if constexpr (j < DA) load_a(j, std::integral_constant<int, j % NA>{});
+        if constexpr (!P3 && j < DA) load_a(j, std::integral_constant<int, j % NA>{});
         load_b(j, std::integral_constant<int, j % NB>{});
     });
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    if constexpr (P3) read_af(0, std::integral_constant<int, 0>{});
     int it = 0;
     for (; it + U <= iters; it += U) {
         static_for<U>([&](auto ic) { body(it + decltype(ic)::value, ic); });
@@ -429,8 +447,9 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
 // in L2.  Where segments share an expert's weights the hint is left off so that L2 serves the re-reads.
 template <int TCAP, bool GATEUP, int WF, bool STREAM>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
-    // two token-tile stages; at least 8 KiB per wave for the epilogue's store staging
-    __shared__ __attribute__((aligned(16))) char lds[(2 * TCAP * 32 * 128) > 32768 ? (2 * TCAP * 32 * 128) : 32768];
+    // two token-tile stages (three for the 7- and 8-tile variants); at least 8 KiB per wave for the
+    // epilogue's store staging
+    __shared__ __attribute__((aligned(16))) char lds[((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) > 32768 ? ((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) : 32768];
     if (b.k.go != nullptr && *b.k.go == 0) return;      // a closed gate: this launch is skipped as a whole
     int ct, kq;
     moe_unit un;
