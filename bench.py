@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2019684508, "cfg4": 1913245597, "cfg3_be": 3651180041, "cfg5": 2694489140,
-                          "cfg4_mxfp4": 516002341, "cfg3_be_mxfp4": 1539863417}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2015510590, "cfg4": 1916501882, "cfg3_be": 3336284064, "cfg5": 2029952310,
+                          "cfg4_mxfp4": 515872653, "cfg3_be_mxfp4": 1542360123}
 
 
 def log(*a):
