@@ -153,8 +153,8 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     }
     // ---- token rows this thread stages into LDS (A operand): row tid/8 + 32*j, slot tid%8 ----
     const int srow = tid >> 3, sslot = tid & 7;
-    // Addressed as a wave-uniform 64-bit base plus a 32-bit byte offset per row (the host checks
-    // that x and act stay below 4 GiB), which halves the registers the row table costs.
+    // Addressed as a wave-uniform 64-bit base plus a 32-bit offset per row in units of 16 bytes (the
+    // host checks that x and act stay below 64 GiB), which halves the registers the row table costs.
     const char *abase = (const char *)p.a_src + ((long)kq * Kg + sslot * 8) * 2;
     unsigned aoff[T];
     static_for<T>([&](auto jc) {
@@ -163,7 +163,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         unsigned src_row;
         if (GATEUP) src_row = (unsigned)(p.perm[un.row0 + r] / p.kdiv);
         else src_row = (unsigned)(un.row0 + r);
-        aoff[j] = src_row * (unsigned)p.lda * 2u;
+        aoff[j] = src_row * ((unsigned)p.lda >> 3);        // in 16-byte units: lda is a multiple of 64 elements
     });
 
     f32x16 acc[T][2];
@@ -187,7 +187,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         const int itc = min(it, iters - 1);
         static_for<T>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            a_reg[S * T + j] = *reinterpret_cast<const u32x4 *>(abase + (aoff[j] + (unsigned)itc * 128u));
+            a_reg[S * T + j] = *reinterpret_cast<const u32x4 *>(abase + ((unsigned long)(aoff[j] + (unsigned)itc * 8u) << 4));
         });
     };
     auto store_a = [&](int stage, auto setc) {

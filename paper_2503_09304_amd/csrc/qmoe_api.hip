@@ -49,9 +49,9 @@ bool config_ok(const moe_config *c, const char **why) {
     if (c->down_ksplit != 0 && c->down_ksplit != 1 && c->down_ksplit != 4) { *why = "down_ksplit must be 0, 1 or 4"; return false; }
     if (c->down_ksplit == 4 && (c->dtype != MOE_BF16 || c->F % 256)) { *why = "down_ksplit 4 needs bf16 and F a multiple of 256"; return false; }
     if ((int64_t)c->max_tokens * c->k >= (int64_t)1 << 31) { *why = "max_tokens*k must be below 2^31"; return false; }
-    if (c->dtype == MOE_BF16 && ((int64_t)c->max_tokens * c->H * 2 >= (int64_t)1 << 32 ||
-                                 (int64_t)c->max_tokens * c->k * c->F * 2 >= (int64_t)1 << 32)) {
-        *why = "bf16: x (max_tokens*H) and the activation (max_tokens*k*F) must each stay below 4 GiB";
+    if (c->dtype == MOE_BF16 && ((int64_t)c->max_tokens * c->H * 2 >= (int64_t)1 << 36 ||
+                                 (int64_t)c->max_tokens * c->k * c->F * 2 >= (int64_t)1 << 36)) {
+        *why = "bf16: x (max_tokens*H) and the activation (max_tokens*k*F) must each stay below 64 GiB";
         return false;
     }
     return true;

@@ -117,3 +117,26 @@ def test_cfg4_decode_with_4bit_weights_full_size():
     nu = g.ctx.cursor.n_units
     h = GpuLayer(inp, mx).full(tuple(range(1, nu)))
     assert torch.equal(bits(h.y), bits(g.y))
+
+
+def test_activation_larger_than_4_gib():
+    """Rows of the SwiGLU activation beyond the first 4 GiB: the down projection addresses its token
+    rows with 32-bit offsets counted in 16-byte units, so the last experts' rows lie past what a
+    32-bit byte offset reaches.  Every sampled token passes through all eight experts."""
+    cfg = wl.scaled(wl.CONFIGS["cfg5"], name="act_5gib", N=80000, n_ls=10000, H=128, F=4096, E=8, k=8,
+                    seed=7711, bias_kind="none", bias_arg=0.0)
+    assert cfg.A * cfg.F * 2 > 1 << 32
+    inp = wl.make_inputs(cfg)
+    say("case", wl.describe(cfg))
+    g = GpuLayer(inp, DevWeights(inp.w).packed()).full()
+    r = g.fetch("logits", "topk_idx", "counts", "perm", "y")
+    lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows, logits=r["logits"].astype(np.float64))
+    assert np.array_equal(r["topk_idx"], lay.idx) and np.array_equal(r["counts"], lay.cnt) and np.array_equal(r["perm"], lay.perm)
+    toks = sample(cfg, 24)
+    e = rel_err(wl.as_f64(r["y"])[toks], lay.y_tokens_direct(toks))
+    say(f"  y rel err on {len(toks)} tokens {e:.3e}")
+    assert e <= 2e-2
+    units = g.ctx.units()
+    high = [i for i, u in enumerate(units) if u[2] * cfg.F * 2 >= 1 << 32]
+    assert len(high) > 100
+    assert_bit_identical(inp, (high[0], high[len(high) // 2]), base=g)
