@@ -96,6 +96,34 @@ hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStrea
     return hipGetLastError();
 }
 
+// Columns per wave of a gate-up launch.  A workgroup stays on its CU for the whole of K, so a launch
+// costs whole rounds of the chip's CUs, and a weight-streaming launch moves bytes in proportion to
+// rounds x columns per workgroup.  Narrower waves (28 .. 16 columns on the 32-wide MFMA; the idle MFMA
+// rows cost nothing where the stream is the bound) are taken when they make the last round full:
+// 8 experts x 14336 columns are 896 workgroups of 128 columns = 3.5 rounds of 256 CUs, but exactly 4
+// rounds of 112 columns (decode gate-up 0.321 -> 0.293 ms).  Only segments of at most 3 token tiles
+// are bound by the stream alone: from 4 tiles on an iteration takes as long for 28 columns as for 32,
+// launches whose segments share weights are MFMA-bound, and with 4-bit weights an iteration's
+// conversions, not its bytes, set the pace (decode gate-up 0.109 -> 0.112 ms); those keep 32.
+static int gate_up_wave_columns(bool stream, int wfmt, int tiles, int nseg, int F) {
+    if (!stream || tiles > 3 || wfmt == bf16k::WF_MXFP4) return 32;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 256;
+        cus = v;
+    }
+    int best = 32;
+    long best_cost = 0;
+    for (int cw = 32; cw >= 16; cw -= 4) {
+        const long wgs = (long)nseg * ((F + 4 * cw - 1) / (4 * cw));
+        if (wgs <= cus && cw < 32) break;            // a single round: nothing to even out
+        const long cost = (wgs + cus - 1) / cus * cw;
+        if (cw == 32 || cost < best_cost) { best = cw; best_cost = cost; }
+    }
+    return best;
+}
+
 void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &dn_in, hipStream_t s) {
     BArgs b{};
     b.ksplit = 1;
@@ -145,7 +173,8 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     if (stream) std::stable_sort(b.seg, b.seg + b.nseg, [](const Seg &x, const Seg &y) { return x.rows > y.rows; });
 
     b.k = gu_in;
-    b.k.col_tiles = (a.F + 127) / 128;
+    b.k.cw = a.wave_cols ? a.wave_cols : gate_up_wave_columns(stream, a.wfmt, tiles, (int)n, a.F);
+    b.k.col_tiles = (a.F + 4 * b.k.cw - 1) / (4 * b.k.cw);
     auto launch = [&](bool gateup) {
         if (a.wfmt == bf16k::WF_MXFP4) bf16k::launch_expert_kernels<bf16k::WF_MXFP4>(gateup, tiles, stream, b, s);
         else if (a.wfmt == bf16k::WF_PACKED) bf16k::launch_expert_kernels<bf16k::WF_PACKED>(gateup, tiles, stream, b, s);
@@ -154,6 +183,7 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch(true); }
 
     b.k = dn_in;
+    b.k.cw = 32;
     b.k.col_tiles = (a.H + 255) / 256;
     if (a.ksplit == 4 && a.partial != nullptr) {
         b.ksplit = 4;

@@ -56,6 +56,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
@@ -96,13 +97,19 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     // during iteration it, and so may read the first fragments of tile it+1 before the iteration's
     // barrier; the LDS latency after the barrier disappears from the MFMA stream.
     constexpr bool P3 = T >= 7;
-    constexpr int CPW = GATEUP ? 32 : 64;  // output columns per wave
+    // Output columns per wave.  Gate-up: 32, or fewer (p.cw, a multiple of 4) on launches whose
+    // workgroup count would otherwise end in a partly filled round of the chip; the wave's MFMA rows
+    // beyond p.cw repeat its last weight row and are dropped in the epilogue.
+    const int cpw = GATEUP ? p.cw : 64;
     const int rows = un.rows;
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int lr = l & 31, lh = l >> 5;
     const int Kg = p.K / ksplit;           // this workgroup's K range: [kq*Kg, (kq+1)*Kg)
     const int iters = Kg / 64;
-    const int col_base = ct * (4 * CPW) + w * CPW;
+    const int col_base = ct * (4 * cpw) + w * cpw;
+    // gate-up: the weight row of this lane, and its place in the 32-row tiles of the packed formats
+    const int grow = min(col_base + min(lr, cpw - 1), p.ncols - 1);
+    const int gnt = grow >> 5, grr = grow & 31;
 
     // ---- weight rows of this lane (B operand) ----
     // Row-major: lane = (row l%32, k-half l/32), 16 elements per k-step, 64 per iteration.
@@ -119,18 +126,19 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     const char *sptr[2];                     // MXFP4 scales
     if constexpr (MX) {
         const int ntiles = p.ncols >> 5;
-        const int nt0 = min(col_base >> 5, ntiles - 1);
-        const int nt1 = GATEUP ? nt0 : min((col_base >> 5) + 1, ntiles - 1);
+        const int nt0 = GATEUP ? gnt : min(col_base >> 5, ntiles - 1);
+        const int nt1 = GATEUP ? gnt : min((col_base >> 5) + 1, ntiles - 1);
+        const int rr = GATEUP ? grr : lr;
         const long kblocks = p.K >> 6;                              // iterations per row tile
         const char *c0 = (const char *)p.b0 + (long)un.expert * (p.b_estride >> 1);
         const char *c1 = GATEUP ? (const char *)p.b1 + (long)un.expert * (p.b_estride >> 1) : c0;
         const char *s0 = (const char *)p.s0 + (long)un.expert * (p.b_estride >> 5);
         const char *s1 = GATEUP ? (const char *)p.s1 + (long)un.expert * (p.b_estride >> 5) : s0;
         const long it0 = (long)kq * (Kg >> 6);
-        cptr[0] = c0 + ((nt0 * kblocks + it0) * 64 + l) * 16;
-        cptr[1] = c1 + ((nt1 * kblocks + it0) * 64 + l) * 16;
-        sptr[0] = s0 + ((nt0 * kblocks + it0) * 32 + lr) * 2;
-        sptr[1] = s1 + ((nt1 * kblocks + it0) * 32 + lr) * 2;
+        cptr[0] = c0 + ((nt0 * kblocks + it0) * 64 + lh * 32 + rr) * 16;
+        cptr[1] = c1 + ((nt1 * kblocks + it0) * 64 + lh * 32 + rr) * 16;
+        sptr[0] = s0 + ((nt0 * kblocks + it0) * 32 + rr) * 2;
+        sptr[1] = s1 + ((nt1 * kblocks + it0) * 32 + rr) * 2;
         bptr[0] = bptr[1] = nullptr;
     } else {
         cptr[0] = cptr[1] = sptr[0] = sptr[1] = nullptr;
@@ -139,13 +147,13 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         if (PACKED) {
             const int ntiles = p.ncols >> 5;
             const long tile_elems = (long)p.K * 32;
-            const long koff = (long)kq * (Kg / 16) * 512 + l * 8;
-            const int nt0 = min(col_base >> 5, ntiles - 1);
-            const int nt1 = GATEUP ? nt0 : min((col_base >> 5) + 1, ntiles - 1);
+            const long koff = (long)kq * (Kg / 16) * 512 + (lh * 32 + (GATEUP ? grr : lr)) * 8;
+            const int nt0 = GATEUP ? gnt : min(col_base >> 5, ntiles - 1);
+            const int nt1 = GATEUP ? gnt : min((col_base >> 5) + 1, ntiles - 1);
             bptr[0] = b0 + nt0 * tile_elems + koff;
             bptr[1] = b1 + nt1 * tile_elems + koff;
         } else {
-            const int c0 = min(col_base + lr, p.ncols - 1);
+            const int c0 = GATEUP ? grow : min(col_base + lr, p.ncols - 1);
             const int c1 = GATEUP ? c0 : min(col_base + 32 + lr, p.ncols - 1);
             bptr[0] = b0 + (long)c0 * p.K + kq * Kg + lh * 8;
             bptr[1] = b1 + (long)c1 * p.K + kq * Kg + lh * 8;
@@ -175,7 +183,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 
     // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
     // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
-    constexpr int DA = T >= 7 ? 1 : D;   // token pieces: same distance, or 1 where registers are scarce
+    constexpr int DA = T >= 7 ? 1 : (T >= 5 && D > 2 ? 2 : D);   // token pieces: same distance, or 1 where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
     bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]; MXFP4: set 0 only, the operands of the current iteration
@@ -360,13 +368,26 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         });
         __builtin_amdgcn_s_waitcnt(0xc07f);   // this wave's LDS writes have landed (lgkmcnt 0)
         __builtin_amdgcn_wave_barrier();
-        const int f0 = col_base + (l & 3) * 8;
+        if (cpw == 32) {
+            const int f0 = col_base + (l & 3) * 8;
 #pragma unroll
-        for (int j = 0; j < 2 * T; ++j) {
-            const int i = (l >> 2) + 16 * j;
-            if (i < rows && f0 < p.ncols) {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(st + i * 32 + (l & 3) * 8);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + f0));
+            for (int j = 0; j < 2 * T; ++j) {
+                const int i = (l >> 2) + 16 * j;
+                if (i < rows && f0 < p.ncols) {
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(st + i * 32 + (l & 3) * 8);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + f0));
+                }
+            }
+        } else {
+            // narrower waves start at multiples of 4 columns: 8-byte stores of the first cpw columns
+            const int fo = (l & 7) * 4;
+#pragma unroll
+            for (int j = 0; j < 4 * T; ++j) {
+                const int i = (l >> 3) + 8 * j;
+                if (i < rows && fo < cpw && col_base + fo < p.ncols) {
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(st + i * 32 + fo);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>((__bf16 *)p.dst + (long)(un.row0 + i) * p.ldd + col_base + fo));
+                }
             }
         }
     } else {
@@ -458,8 +479,8 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
     if (TCAP >= 8 && t_cnt > 7) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 7 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 5 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 5 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else expert_tile<1, GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);

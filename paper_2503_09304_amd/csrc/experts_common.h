@@ -19,6 +19,7 @@ struct KArgs {
     unsigned u0;
     int nu;                 // units in this launch
     int col_tiles;
+    int cw;                 // bf16 gate-up: output columns per wave (32, or 28 .. 16 in steps of 4)
     const int32_t *go;      // gated launches: the workgroups do nothing unless *go != 0 (nullptr: not gated)
 };
 

@@ -126,6 +126,7 @@ struct moe_ctx {
     int32_t *pinned_dev;   // the device's address of the same memory
     int32_t seq;           // sequence number of the last report asked for
     int spin_ms;           // how long moe_permute polls for the report before it waits for the stream
+    int wave_cols;         // 0: the launch policy picks the gate-up wave width; else forced (tests)
     const void *x;
     moe_weights w;
     qmoe::Profiler prof;
@@ -235,6 +236,11 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     if (const char *v = getenv("QMOE_REPORT_SPIN_MS")) {      // for tests of the fall-back: 0 = do not poll at all
         const long ms = strtol(v, nullptr, 10);
         if (ms >= 0 && ms <= 60000) c->spin_ms = (int)ms;
+    }
+    c->wave_cols = 0;
+    if (const char *v = getenv("QMOE_GATE_UP_WAVE_COLUMNS")) {   // for tests: every bf16 gate-up launch uses this width
+        const long cw = strtol(v, nullptr, 10);
+        if (cw >= 16 && cw <= 32 && cw % 4 == 0) c->wave_cols = (int)cw;
     }
     c->prof_on = false;
     c->x = nullptr;
@@ -391,6 +397,7 @@ static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *
     a.wfmt = w->layout == MOE_W_MXFP4 ? 2 : (w->layout == MOE_W_PACKED ? 1 : 0);
     a.S1 = w->S1; a.S3 = w->S3; a.S2 = w->S2;
     a.ksplit = ctx->lay.has_partial ? 4 : 1;
+    a.wave_cols = ctx->wave_cols;
     a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
     a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
     const moe_unit *un = ctx->units.data();

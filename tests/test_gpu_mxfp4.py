@@ -106,3 +106,18 @@ def test_4bit_argument_checks():
     with pytest.raises(q.MoeError) as e:
         g.ctx.route(g.x, bad, None, n_tokens=cfg.N)        # a scale pointer is missing
     assert e.value.code == q.MOE_E_ARG
+
+
+def test_4bit_weights_with_narrow_gate_up_waves(monkeypatch):
+    """The launch policy keeps 32-column waves for 4-bit weights, but the kernels take any width: a
+    forced width of 20 gives the bits of the default."""
+    cfg = wl.LayerConfig("q6", dtype="bf16", seed=947, E=6, k=2, H=192, F=448, N=333, n_ls=77, chunk_rows=64)
+    inp = wl.make_inputs(cfg, weights={})
+    mx = DevWeightsMX(wl.make_weights_mxfp4(cfg)).packed()
+    ref = GpuLayer(inp, mx).full()
+    monkeypatch.setenv("QMOE_GATE_UP_WAVE_COLUMNS", "20")
+    g = GpuLayer(inp, mx)                          # the variable is read when the context is created
+    monkeypatch.delenv("QMOE_GATE_UP_WAVE_COLUMNS")
+    g.full((2, 5))
+    assert torch.equal(g.ctx.get("act").view(torch.int16), ref.ctx.get("act").view(torch.int16))
+    assert torch.equal(g.y.view(torch.int16), ref.y.view(torch.int16))

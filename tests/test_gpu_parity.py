@@ -326,3 +326,21 @@ def test_permute_falls_back_to_a_stream_wait_when_it_may_not_poll(monkeypatch):
         g.full()
         assert g.ctx.cursor.n_units == ref.ctx.cursor.n_units
         assert torch.equal(bits(g.y), bits(ref.y))
+
+
+@pytest.mark.parametrize("cw", [28, 20, 16])
+def test_narrow_gate_up_waves_give_the_same_bits(monkeypatch, cw):
+    """A gate-up launch may give each wave fewer than 32 columns (chosen per launch from the number of
+    workgroups; QMOE_GATE_UP_WAVE_COLUMNS forces a width for every launch of a context).  Which wave
+    computes a column never changes its arithmetic: same bits as with 32, row-major and packed, with F
+    not a multiple of the narrower workgroup width, and against the oracle."""
+    cfg = wl.LayerConfig(f"cw{cw}", dtype="bf16", seed=3100 + cw, E=6, k=2, H=192, F=448, N=333, n_ls=77, chunk_rows=64)
+    inp = wl.make_inputs(cfg)
+    ref, _ = check_layer(inp)
+    for dw in (ref.dw, DevWeights(inp.w).packed()):
+        monkeypatch.setenv("QMOE_GATE_UP_WAVE_COLUMNS", str(cw))
+        g = GpuLayer(inp, dw)                      # the variable is read when the context is created
+        monkeypatch.delenv("QMOE_GATE_UP_WAVE_COLUMNS")
+        g.full((3, 7))
+        assert torch.equal(bits(g.ctx.get("act")), bits(ref.ctx.get("act")))
+        assert torch.equal(bits(g.y), bits(ref.y))
