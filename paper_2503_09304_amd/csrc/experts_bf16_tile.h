@@ -183,7 +183,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 
     // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
     // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
-    constexpr int DA = T >= 7 ? 1 : (T >= 5 && D > 2 ? 2 : D);   // token pieces: same distance, or 1 where registers are scarce
+    constexpr int DA = T >= 7 ? 1 : (T >= 5 && D > 2 ? 2 : D);   // token pieces: same distance, or less where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
     bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]; MXFP4: set 0 only, the operands of the current iteration
@@ -476,7 +476,8 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     moe_unit un;
     if (!map_block<STREAM>(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
-    // Prefetch distance: 3 iterations where the register file allows it, 2 for the 8-tile variant.
+    // Prefetch distance of the weights: 3 iterations where the register file allows it, 2 for the 7- and 8-tile
+    // and the 2-tile variants; the token pieces of the 5- and 6-tile variants stay 2 ahead.
     if (TCAP >= 8 && t_cnt > 7) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 7 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
