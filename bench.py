@@ -269,15 +269,15 @@ def main() -> int:
     ap.add_argument("--serve-max-prompt", type=int, default=512)
     ap.add_argument("--serve-max-out", type=int, default=32)
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rowmajor", action="store_true", help="keep the weights row-major (default: packed at load)")
     ap.add_argument("--weights", default="bf16", choices=["bf16", "mxfp4"],
                     help="expert weight format: bf16 (the headline workload) or 4-bit microscaling FP4")
-    ap.add_argument("--latency-trials", type=int, default=40,
+    ap.add_argument("--latency-trials", type=int, default=100,
                     help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
     ap.add_argument("--units-per-call", type=int, default=4)
     ap.add_argument("--lookahead", type=int, default=1)
@@ -372,6 +372,15 @@ def main() -> int:
         for i in range(4):
             acc[i] += ev[i].elapsed_time(ev[i + 1]) / 5
     stages = dict(zip(("route_ms", "permute_ms", "experts_ms", "combine_ms"), (round(v, 4) for v in acc)))
+    # ---- spread of single steps (events around each step; the timed region above is the figure of record)
+    n_each = max(1, min(args.steps, 100))
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
+    for a, b in pairs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    each = np.array([a.elapsed_time(b) for a, b in pairs])
+    step_ms = {"median": round(float(np.median(each)), 4), "min": round(float(each.min()), 4),
+               "max": round(float(each.max()), 4), "n": n_each}
 
     ksplit = 4 if (cfg.F % 256 == 0 and cfg.N * cfg.k <= 256 * cfg.E) else 1
     gu_ms, gu_n = prof["gate_up"]
@@ -465,6 +474,7 @@ def main() -> int:
                    "units": int(g.ctx.cursor.n_units)},
         "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
         "stages_ms": stages,
+        "step_ms": step_ms,
         "roofline": roof,
         "ls_first_in_mixed_batch": ls_first,
         "ls_latency_under_be_load": lat,
