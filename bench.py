@@ -54,7 +54,7 @@ def pct(v, p):
     return float(np.percentile(np.asarray(v), p))
 
 
-def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be_ksplit=0, seed=77):
+def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be_ksplit=0, seed=77, ls_own_stream=False):
     """LS completion latency when a BE prompt is in flight (cfg3): the BE context is fed
     `units_per_call` work units per moe_expert_run with at most `lookahead` calls outstanding; at a
     seeded offset into the BE layer an LS batch arrives, the host stops feeding BE, runs the LS
@@ -68,12 +68,32 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
     def run_ls():
         ls.route_permute(); ls.run(); ls.combine(q.MOE_CLASS_LS)
 
+    # With --ls-own-stream the arriving LS batch goes to a stream of its own (default priority): its
+    # kernels need not wait for the BE launch in flight to drain, they take the CUs that launch's
+    # last workgroups leave free.
+    side = torch.cuda.Stream() if ls_own_stream else None
+
+    def run_ls_arrived():
+        """LS batch at its arrival under BE load; returns when the host sees its combine done."""
+        if side is None:
+            run_ls()
+            ev = torch.cuda.Event(); ev.record()
+        else:
+            with torch.cuda.stream(side):
+                run_ls()
+                ev = torch.cuda.Event(); ev.record()
+        ev.synchronize()
+
     def run_be_all():
         be.route_permute(); be.run(); be.combine()
 
     for _ in range(3):
         run_be_all(); run_ls()
     torch.cuda.synchronize()
+    if side is not None:                      # first use of the stream stays out of the measurement
+        with torch.cuda.stream(side):
+            run_ls()
+        torch.cuda.synchronize()
     # references: BE alone, LS alone on an idle GPU
     t = []
     for _ in range(5):
@@ -145,9 +165,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
             if not arrived and now >= off:
                 arrived = True
                 waited_units.append(len(pending) * units_per_call)
-                run_ls()
-                ev = torch.cuda.Event(); ev.record()
-                ev.synchronize()
+                run_ls_arrived()
                 t_done = time.perf_counter() - t0
                 continue
             while pending and pending[0].query():
@@ -177,8 +195,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         while time.perf_counter() - t0 < off:
             pass
         be.ctx.expert_stop()
-        run_ls()
-        ev = torch.cuda.Event(); ev.record(); ev.synchronize()
+        run_ls_arrived()
         lat_dev.append(time.perf_counter() - t0 - off)
         while rc != q.MOE_DONE:
             rc = be.ctx.expert_collect()
@@ -192,6 +209,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
     return {
         "workload": "cfg3: 3584-token BE prompt in flight (28 units of <=256 rows), 512-token LS batch arrives",
         "trials": trials, "units_per_call": units_per_call, "lookahead_calls": lookahead,
+        "ls_stream": "own" if ls_own_stream else "shared with BE",
         "ls_latency_ms": {"p50": ms(pct(lat, 50)), "p99": ms(pct(lat, 99)), "max": ms(max(lat))},
         "ls_alone_idle_gpu_ms": round(ls_alone_ms, 4),
         "ls_latency_no_preemption_ms": {"p50": ms(pct(lat_nopre, 50)), "p99": ms(pct(lat_nopre, 99))},
@@ -434,6 +452,10 @@ def main() -> int:
     if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx:
         lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
                          be_ksplit=args.be_ksplit)
+        own = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
+                         be_ksplit=args.be_ksplit, ls_own_stream=True)
+        lat["ls_on_own_stream"] = {"ls_latency_ms": own["ls_latency_ms"], "device_stop": own["device_stop"],
+                                   "be_output_bit_identical_after_resume": own["be_output_bit_identical_after_resume"]}
         log("LS latency under BE load:", json.dumps(lat))
 
     # ---- the oracle, as it stands, on a bounded sample of the same workload
