@@ -147,7 +147,10 @@ typedef enum {
 size_t moe_workspace_bytes(const moe_config *cfg);
 
 /* Creates a context over `workspace` ([device], 256-byte aligned, >= moe_workspace_bytes(cfg)).
- * Touches no GPU state.  The workspace must outlive the context. */
+ * Touches no GPU state.  The workspace must outlive the context.  Two environment variables are read
+ * here, both for tests: QMOE_REPORT_SPIN_MS (see moe_permute) and QMOE_GATE_UP_WAVE_COLUMNS (16, 20,
+ * 24, 28 or 32: every bf16 gate-up launch of the context gives each wave that many output columns
+ * instead of the width the launch would pick; results do not depend on it). */
 int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_bytes, moe_ctx **out);
 
 /* Frees the host object (and its pinned buffer).  Does not wait for enqueued work. */
