@@ -45,7 +45,7 @@ def gate_up_bytes(cfg, counts, es, ws):
 
 def down_bytes(cfg, counts, es, ws, ksplit):
     touched = int((counts.sum(1) > 0).sum())
-    planes = 4 * cfg.A * cfg.H * 4 * 2 if ksplit == 4 else 0     # partial planes written, then read
+    planes = ksplit * cfg.A * cfg.H * 4 * 2 if ksplit > 1 else 0     # partial planes written, then read
     return int(touched * cfg.H * cfg.F * ws) + cfg.A * cfg.F * es + cfg.A * cfg.H * 4 + planes
 
 
@@ -299,7 +299,7 @@ def main() -> int:
                     help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
     ap.add_argument("--units-per-call", type=int, default=4)
     ap.add_argument("--lookahead", type=int, default=1)
-    ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 4],
+    ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 2, 4],
                     help="down_ksplit of the BE context in the latency scenario (0 = from the configuration)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the yardstick for HBM byte counters")
@@ -400,7 +400,16 @@ def main() -> int:
     step_ms = {"median": round(float(np.median(each)), 4), "min": round(float(each.min()), 4),
                "max": round(float(each.max()), 4), "n": n_each}
 
-    ksplit = 4 if (cfg.F % 256 == 0 and cfg.N * cfg.k <= 256 * cfg.E) else 1
+    # what down_ksplit = 0 picks (include/qmoe.h): the fewest K ranges that give every CU a workgroup
+    ksplit = 1
+    if cfg.N * cfg.k <= 256 * cfg.E:
+        wgs = cfg.E * ((cfg.H + 255) // 256)
+        if wgs >= 256:
+            ksplit = 1
+        elif 2 * wgs >= 256 and cfg.F % 128 == 0:
+            ksplit = 2
+        else:
+            ksplit = 4 if cfg.F % 256 == 0 else (2 if cfg.F % 128 == 0 else 1)
     gu_ms, gu_n = prof["gate_up"]
     dn_ms = prof["down"][0] + prof["down_reduce"][0]
     gu_avg_ms = gu_ms / max(gu_n, 1)

@@ -65,9 +65,12 @@ typedef struct {
     int32_t chunk_rows; /* C: most rows of one work unit, 1..256                                */
     int32_t max_tokens; /* capacity of the context, N <= max_tokens, max_tokens*k < 2^31        */
     int32_t down_ksplit; /* K-split of the down projection: 0 = choose from the configuration, 1 = none,
-                            4 = four K quarters added in a fixed order (bf16, F % 256 == 0 only).
-                            0 picks 4 when F % 256 == 0 and max_tokens*k <= 256*E (weight-streaming
-                            shapes, where the split supplies the parallelism), else 1.  Choose 4 for a
+                            2 or 4 = that many contiguous K ranges, each summed on its own, added in
+                            ascending order ((p0+p1)+p2)+p3 (bf16, F % (64*down_ksplit) == 0 only).
+                            0 picks 1 unless max_tokens*k <= 256*E (weight-streaming shapes, where
+                            the split supplies the parallelism): there it picks the fewest ranges
+                            (1, 2, 4) for which E * ceil(H/256) * ranges reaches the 256 compute
+                            units, as far as F allows.  Choose 4 for a
                             context whose batches are fed a few units per call so that they can be
                             stopped quickly: a launch of few units has only H/256 workgroups per unit in
                             the down projection without the split.  Part of the

@@ -10,7 +10,7 @@ namespace {
 using bf16k::BArgs;
 using bf16k::f32x4;
 
-// out[r,:] = ((p0 + p1) + p2) + p3 for the rows of the launch.
+// out[r,:] = ((p0 + p1) + p2) + p3 (or p0 + p1 with two planes) for the rows of the launch.
 __global__ __launch_bounds__(256) void reduce_planes(const BArgs b, const float *__restrict__ part, float *__restrict__ out, int H) {
     if (b.k.go != nullptr && *b.k.go == 0) return;
     const long plane = b.plane;
@@ -26,11 +26,16 @@ __global__ __launch_bounds__(256) void reduce_planes(const BArgs b, const float 
         const long off = ((long)un.row0 * H) + i * 4;
         const f32x4 a = *reinterpret_cast<const f32x4 *>(part + off);
         const f32x4 p1 = *reinterpret_cast<const f32x4 *>(part + plane + off);
-        const f32x4 p2 = *reinterpret_cast<const f32x4 *>(part + 2 * plane + off);
-        const f32x4 p3 = *reinterpret_cast<const f32x4 *>(part + 3 * plane + off);
         f32x4 v;
+        if (b.ksplit == 4) {
+            const f32x4 p2 = *reinterpret_cast<const f32x4 *>(part + 2 * plane + off);
+            const f32x4 p3 = *reinterpret_cast<const f32x4 *>(part + 3 * plane + off);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = ((a[q] + p1[q]) + p2[q]) + p3[q];
+            for (int q = 0; q < 4; ++q) v[q] = ((a[q] + p1[q]) + p2[q]) + p3[q];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = a[q] + p1[q];
+        }
         *reinterpret_cast<f32x4 *>(out + off) = v;
     }
 }
@@ -185,8 +190,8 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     b.k = dn_in;
     b.k.cw = 32;
     b.k.col_tiles = (a.H + 255) / 256;
-    if (a.ksplit == 4 && a.partial != nullptr) {
-        b.ksplit = 4;
+    if (a.ksplit > 1 && a.partial != nullptr) {
+        b.ksplit = a.ksplit;
         b.plane = a.plane;
         b.k.dst = a.partial;
         { Scope sc(a.prof, MOE_PROF_DOWN, s); launch(false); }

@@ -46,8 +46,8 @@ bool config_ok(const moe_config *c, const char **why) {
     if (c->dtype == MOE_BF16 && (c->H % 64 || c->F % 64)) { *why = "bf16 needs H and F multiples of 64"; return false; }
     if (c->chunk_rows < 1 || c->chunk_rows > qmoe::kMaxChunkRows) { *why = "chunk_rows out of range (1..256)"; return false; }
     if (c->max_tokens < 0) { *why = "max_tokens negative"; return false; }
-    if (c->down_ksplit != 0 && c->down_ksplit != 1 && c->down_ksplit != 4) { *why = "down_ksplit must be 0, 1 or 4"; return false; }
-    if (c->down_ksplit == 4 && (c->dtype != MOE_BF16 || c->F % 256)) { *why = "down_ksplit 4 needs bf16 and F a multiple of 256"; return false; }
+    if (c->down_ksplit != 0 && c->down_ksplit != 1 && c->down_ksplit != 2 && c->down_ksplit != 4) { *why = "down_ksplit must be 0, 1, 2 or 4"; return false; }
+    if (c->down_ksplit > 1 && (c->dtype != MOE_BF16 || c->F % (64 * c->down_ksplit))) { *why = "down_ksplit 2 or 4 needs bf16 and F a multiple of 64 * down_ksplit"; return false; }
     if ((int64_t)c->max_tokens * c->k >= (int64_t)1 << 31) { *why = "max_tokens*k must be below 2^31"; return false; }
     if (c->dtype == MOE_BF16 && ((int64_t)c->max_tokens * c->H * 2 >= (int64_t)1 << 36 ||
                                  (int64_t)c->max_tokens * c->k * c->F * 2 >= (int64_t)1 << 36)) {
@@ -61,13 +61,20 @@ bool config_ok(const moe_config *c, const char **why) {
 struct Layout {
     size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, go, units, wgt, act, out, partial, total;
     bool has_partial;
+    int ksplit;            // 1, 2 or 4: K ranges of the down projection, one partial plane each
     uint32_t max_units;
 };
 
 int down_ksplit(const moe_config &c) {
-    if (c.dtype != MOE_BF16 || c.F % 256) return 1;
     if (c.down_ksplit) return c.down_ksplit;
-    return (int64_t)c.max_tokens * c.k <= (int64_t)256 * c.E ? 4 : 1;
+    if (c.dtype != MOE_BF16 || (int64_t)c.max_tokens * c.k > (int64_t)256 * c.E) return 1;
+    // Weight-streaming shapes: a launch has one workgroup per (expert, 256 columns, K range).  The
+    // fewest ranges that give each of the 256 CUs a workgroup: more ranges only add partial planes
+    // (Mixtral shape, 512 tokens: 2 ranges 0.17 ms, 4 ranges 0.19-0.20 ms, none 0.26 ms).
+    const int64_t wgs = (int64_t)c.E * ((c.H + 255) / 256);
+    if (wgs >= 256) return 1;
+    if (2 * wgs >= 256 && c.F % 128 == 0) return 2;
+    return c.F % 256 == 0 ? 4 : (c.F % 128 == 0 ? 2 : 1);
 }
 
 Layout make_layout(const moe_config &c) {
@@ -95,9 +102,10 @@ Layout make_layout(const moe_config &c) {
     L.wgt = take(((E + 15) / 16 * 16) * (size_t)c.H * 2);
     L.act = take(A * (size_t)c.F * es);
     L.out = take(A * (size_t)c.H * 4);
-    // K-split down projection (bf16, F a multiple of 256): four partial planes shaped like `out`
-    L.has_partial = down_ksplit(c) == 4;
-    L.partial = L.has_partial ? take(4 * A * (size_t)c.H * 4) : 0;
+    // K-split down projection: one partial plane shaped like `out` per K range
+    L.ksplit = down_ksplit(c);
+    L.has_partial = L.ksplit > 1;
+    L.partial = L.has_partial ? take((size_t)L.ksplit * A * (size_t)c.H * 4) : 0;
     L.total = p ? p : kAlign;
     return L;
 }
@@ -396,7 +404,7 @@ static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *
     a.prof = ctx->prof_on ? &ctx->prof : nullptr;
     a.wfmt = w->layout == MOE_W_MXFP4 ? 2 : (w->layout == MOE_W_PACKED ? 1 : 0);
     a.S1 = w->S1; a.S3 = w->S3; a.S2 = w->S2;
-    a.ksplit = ctx->lay.has_partial ? 4 : 1;
+    a.ksplit = ctx->lay.ksplit;
     a.wave_cols = ctx->wave_cols;
     a.partial = ctx->lay.has_partial ? at<float>(ctx, ctx->lay.partial) : nullptr;
     a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;

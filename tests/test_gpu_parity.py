@@ -163,9 +163,9 @@ def test_reduced_size_cases_match_oracle_and_survive_preemption(name, cfg):
             assert_bit_identical(inp, wl.cut_points(cfg.seed + 1, range(1, nu), 3), dev_w=pk, base=gp)
 
 
-@pytest.mark.parametrize("ks", [1, 4])
+@pytest.mark.parametrize("ks", [1, 2, 4])
 def test_down_projection_k_split_is_a_configuration_choice(ks):
-    """Both settings match the oracle and are bit-stable under preemption; auto picks per config."""
+    """Every setting matches the oracle and is bit-stable under preemption; auto picks per config."""
     cfg = wl.LayerConfig("ks", dtype="bf16", seed=930 + ks, E=8, k=2, H=256, F=512, N=700, n_ls=150, chunk_rows=128)
     inp = wl.make_inputs(cfg)
     lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
@@ -182,6 +182,9 @@ def test_down_projection_k_split_is_a_configuration_choice(ks):
         q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 512, q.MOE_BF16, 64, 16, 3))
     with pytest.raises(q.MoeError):
         q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 192, q.MOE_BF16, 64, 16, 4))     # F not a multiple of 256
+    with pytest.raises(q.MoeError):
+        q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 192, q.MOE_BF16, 64, 16, 2))     # nor of 128
+    q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 384, q.MOE_BF16, 64, 16, 2))
     with pytest.raises(q.MoeError):
         q.moe_workspace_bytes(q.MoeConfig(8, 2, 256, 512, q.MOE_F32, 64, 16, 4))
 
