@@ -131,8 +131,9 @@ __device__ __forceinline__ void wave_topk_rank(const float *__restrict__ row, fl
 
 // Gate GEMM and top-k of 16 tokens per workgroup.  NB = number of 16-expert blocks held in
 // registers (E16 <= 16*NB).  The 8 waves split the hidden dimension into 8 contiguous ranges (loads
-// issued 8 k-steps at a time), add their partial tiles through LDS in wave order, and then each
-// wave selects the experts of 2 of the 16 tokens.
+// issued 8, 4 or 2 k-steps at a time: few enough registers that at least two workgroups share a CU,
+// which halves the router's time on 8192 tokens x 64 experts), add their partial tiles through LDS
+// in wave order, and then each wave selects the experts of 2 of the 16 tokens.
 template <int NB>
 __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict__ x, const uint16_t *__restrict__ WgT,
                                                       const float *__restrict__ bias, float *__restrict__ logits,
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict
     for (int b = 0; b < NB; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     const uint16_t *xa = x + (long)tok * H + q * 8;
     const uint16_t *wb = WgT + (long)t16 * H + q * 8;
-    constexpr int CH = NB <= 4 ? 8 : 2;   // k-steps whose loads are issued together
+    constexpr int CH = NB == 1 ? 8 : (NB == 2 ? 4 : 2);   // k-steps whose loads are issued together
     for (int s = s0; s < s1; s += CH) {
         bf16x8 a[CH], bv[CH][NB];
 #pragma unroll
