@@ -74,59 +74,82 @@ __device__ __forceinline__ void wave_topk(const float (&v)[kSlots], int l, int E
 // broadcasts.  The selected logits go through `slot_v` / `slot_e` (k entries of LDS, private to the
 // wave) so that lane j holds slot j, and the weights are the same softmax, summed in the same
 // butterfly order, as wave_topk computes.
-__device__ __forceinline__ void wave_topk_rank(const float *__restrict__ row, float *__restrict__ slot_v,
-                                               int32_t *__restrict__ slot_e, int l, int E, int k,
-                                               int32_t *__restrict__ idx_out, float *__restrict__ w_out) {
-    float mine[kSlots];
-    int rank[kSlots];
+template <int NT>
+__device__ __forceinline__ void wave_topk_rank(const float *const (&row)[NT], float (*__restrict__ slot_v)[kMaxTopK],
+                                               int32_t (*__restrict__ slot_e)[kMaxTopK], int l, int E, int k,
+                                               int32_t *const (&idx_out)[NT], float *const (&w_out)[NT]) {
+    // NT tokens of the wave side by side: their LDS reads and shuffles overlap.  idx_out[h] == nullptr:
+    // token h is past the end of the batch (its row holds a copy of the last token) and stores nothing.
+    float mine[NT][kSlots];
+    int rank[NT][kSlots];
 #pragma unroll
-    for (int c = 0; c < kSlots; ++c) {
-        const int e = l + 64 * c;
-        mine[c] = e < E ? row[e] : 0.f;
-        rank[c] = 0;
-    }
+    for (int h = 0; h < NT; ++h)
+#pragma unroll
+        for (int c = 0; c < kSlots; ++c) {
+            const int e = l + 64 * c;
+            mine[h][c] = e < E ? row[h][e] : 0.f;
+            rank[h][c] = 0;
+        }
     const int nslots = (E + 63) >> 6;
     const int E8 = E & ~7;
-    for (int o0 = 0; o0 < E8; o0 += 8) {                 // 8 broadcast reads in flight at a time
-        float ov[8];
+    for (int o0 = 0; o0 < E8; o0 += 8) {                 // 8 broadcast reads per token in flight at a time
+        float ov[NT][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ov[i] = row[o0 + i];
+        for (int h = 0; h < NT; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ov[h][i] = row[h][o0 + i];
 #pragma unroll
         for (int c = 0; c < kSlots; ++c) {
             if (c < nslots) {
                 const int e = l + 64 * c;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) rank[c] += (ov[i] > mine[c] || (ov[i] == mine[c] && o0 + i < e)) ? 1 : 0;
+                for (int h = 0; h < NT; ++h)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        rank[h][c] += (ov[h][i] > mine[h][c] || (ov[h][i] == mine[h][c] && o0 + i < e)) ? 1 : 0;
             }
         }
     }
     for (int o = E8; o < E; ++o) {
-        const float ov = row[o];
 #pragma unroll
-        for (int c = 0; c < kSlots; ++c) {
-            const int e = l + 64 * c;
-            if (c < nslots) rank[c] += (ov > mine[c] || (ov == mine[c] && o < e)) ? 1 : 0;
+        for (int h = 0; h < NT; ++h) {
+            const float ov = row[h][o];
+#pragma unroll
+            for (int c = 0; c < kSlots; ++c) {
+                const int e = l + 64 * c;
+                if (c < nslots) rank[h][c] += (ov > mine[h][c] || (ov == mine[h][c] && o < e)) ? 1 : 0;
+            }
         }
     }
 #pragma unroll
-    for (int c = 0; c < kSlots; ++c) {
-        const int e = l + 64 * c;
-        if (e < E && rank[c] < k) { slot_v[rank[c]] = mine[c]; slot_e[rank[c]] = e; }
-    }
+    for (int h = 0; h < NT; ++h)
+#pragma unroll
+        for (int c = 0; c < kSlots; ++c) {
+            const int e = l + 64 * c;
+            if (e < E && rank[h][c] < k) { slot_v[h][rank[h][c]] = mine[h][c]; slot_e[h][rank[h][c]] = e; }
+        }
     __builtin_amdgcn_s_waitcnt(0xc07f);      // this wave's LDS writes have landed
     __builtin_amdgcn_wave_barrier();
-    const float my_v = l < k ? slot_v[l] : 0.f;
-    const int my_e = l < k ? slot_e[l] : 0;
-    const float top = __shfl(my_v, 0, 64);
-    const float p = l < k ? expf(my_v - top) : 0.f;
-    float s = p;
+    float my_v[NT], p[NT], s[NT];
+    int my_e[NT];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (l < k) {
-        idx_out[l] = my_e;
-        w_out[l] = p / s;
+    for (int h = 0; h < NT; ++h) {
+        my_v[h] = l < k ? slot_v[h][l] : 0.f;
+        my_e[h] = l < k ? slot_e[h][l] : 0;
+        const float top = __shfl(my_v[h], 0, 64);
+        p[h] = l < k ? expf(my_v[h] - top) : 0.f;
+        s[h] = p[h];
     }
-    __builtin_amdgcn_wave_barrier();         // slot_v / slot_e are reused for the wave's next token
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+        for (int h = 0; h < NT; ++h) s[h] += __shfl_xor(s[h], o, 64);
+#pragma unroll
+    for (int h = 0; h < NT; ++h)
+        if (l < k && idx_out[h] != nullptr) {
+            idx_out[h][l] = my_e[h];
+            w_out[h][l] = p[h] / s[h];
+        }
 }
 
 // Gate GEMM and top-k of 16 tokens per workgroup.  NB = number of 16-expert blocks held in
@@ -139,14 +162,16 @@ __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict
                                                       const float *__restrict__ bias, float *__restrict__ logits,
                                                       int32_t *__restrict__ topk_idx, float *__restrict__ topk_w, int N, int H,
                                                       int E, int nb, int k) {
-    __shared__ float red[7][NB][4][64];
+    __shared__ float red[8][NB][4][64];
     __shared__ float lt[16][NB * 16 + 1];
-    __shared__ float slot_v[8][kMaxTopK];
-    __shared__ int32_t slot_e[8][kMaxTopK];
+    __shared__ float sbias[NB * 16];
+    __shared__ float slot_v[8][2][kMaxTopK];
+    __shared__ int32_t slot_e[8][2][kMaxTopK];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const int t16 = l & 15, q = l >> 4;
     int tok = blockIdx.x * 16 + t16;
     if (tok > N - 1) tok = N - 1;
+    if (tid < NB * 16) sbias[tid] = (bias && tid < E) ? bias[tid] : 0.f;   // read after the first barrier
     const int steps = H / 32;
     const int per = (steps + 7) / 8;
     const int s0 = w * per, s1 = min(steps, s0 + per);
@@ -175,38 +200,36 @@ __global__ __launch_bounds__(512) void gate_topk_bf16(const uint16_t *__restrict
             }
         }
     }
-    if (w > 0) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) red[w - 1][b][r][l] = acc[b][r];
-    }
+        for (int r = 0; r < 4; ++r) red[w][b][r][l] = acc[b][r];
     __syncthreads();
-    if (w == 0) {
+    // The NB*4 (expert block, D register) pairs are dealt to the 8 waves; each sum runs over the waves'
+    // partial tiles in wave order.
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            if (b < nb) {
+    for (int j = 0; j < (NB * 4 + 7) / 8; ++j) {
+        const int pr = w + 8 * j;
+        const int b = pr >> 2, r = pr & 3;
+        if (pr < NB * 4 && b < nb) {
+            float v = red[0][b][r][l];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float v = acc[b][r];
-#pragma unroll
-                    for (int ww = 0; ww < 7; ++ww) v += red[ww][b][r][l];
-                    const int e = b * 16 + t16;                 // D: column = expert
-                    const int tl = q * 4 + r;                   // D: row = token (within the 16)
-                    const int t = blockIdx.x * 16 + tl;
-                    const float lv = v + ((bias && e < E) ? bias[e] : 0.f);
-                    lt[tl][e] = lv;
-                    if (e < E && t < N) logits[(long)t * E + e] = lv;
-                }
-            }
+            for (int ww = 1; ww < 8; ++ww) v += red[ww][b][r][l];
+            const int e = b * 16 + t16;                 // D: column = expert
+            const int tl = q * 4 + r;                   // D: row = token (within the 16)
+            const int t = blockIdx.x * 16 + tl;
+            const float lv = v + sbias[e];
+            lt[tl][e] = lv;
+            if (e < E && t < N) logits[(long)t * E + e] = lv;
         }
     }
     __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int tl = w * 2 + h;
-        const int t = blockIdx.x * 16 + tl;
-        if (t < N) wave_topk_rank(lt[tl], slot_v[w], slot_e[w], l, E, k, topk_idx + (long)t * k, topk_w + (long)t * k);
+    const int t0 = blockIdx.x * 16 + w * 2;             // this wave's two tokens
+    if (t0 < N) {
+        const float *const rows[2] = {lt[w * 2], lt[w * 2 + 1]};
+        int32_t *const io[2] = {topk_idx + (long)t0 * k, t0 + 1 < N ? topk_idx + (long)(t0 + 1) * k : nullptr};
+        float *const wo[2] = {topk_w + (long)t0 * k, t0 + 1 < N ? topk_w + (long)(t0 + 1) * k : nullptr};
+        wave_topk_rank<2>(rows, slot_v[w], slot_e[w], l, E, k, io, wo);
     }
 }
 
