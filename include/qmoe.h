@@ -70,7 +70,8 @@ typedef struct {
                             0 picks 1 unless max_tokens*k <= 256*E (weight-streaming shapes, where
                             the split supplies the parallelism): there it picks the fewest ranges
                             (1, 2, 4) for which E * ceil(H/256) * ranges reaches the 256 compute
-                            units, as far as F allows.  Choose 4 for a
+                            units, as far as F allows (with 4-bit weights and decode-sized batches 4
+                            ranges are faster than that choice: set it).  Choose 4 for a
                             context whose batches are fed a few units per call so that they can be
                             stopped quickly: a launch of few units has only H/256 workgroups per unit in
                             the down projection without the split.  Part of the

@@ -103,7 +103,7 @@ def test_cfg4_decode_with_4bit_weights_full_size():
     w4 = wl.make_weights_mxfp4(cfg)
     inp = wl.make_inputs(cfg, weights=oracle.mxfp4_weights_as_bf16(w4))
     mx = DevWeightsMX(w4).packed()
-    g = GpuLayer(inp, mx).full()
+    g = GpuLayer(inp, mx, down_ksplit=4).full()         # four K ranges, as the benchmark sets for this case
     r = g.fetch("logits", "topk_idx", "counts", "perm", "y")
     lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows, logits=r["logits"].astype(np.float64))
     assert np.array_equal(r["topk_idx"], lay.idx) and np.array_equal(r["counts"], lay.cnt) and np.array_equal(r["perm"], lay.perm)
@@ -115,7 +115,7 @@ def test_cfg4_decode_with_4bit_weights_full_size():
     say(f"  cfg4 with 4-bit weights: y rel err {e:.3e} (tol {tol:.3e}; bf16 output rounding alone {floor:.3e})")
     assert e <= tol
     nu = g.ctx.cursor.n_units
-    h = GpuLayer(inp, mx).full(tuple(range(1, nu)))
+    h = GpuLayer(inp, mx, down_ksplit=4).full(tuple(range(1, nu)))
     assert torch.equal(bits(h.y), bits(g.y))
 
 
