@@ -21,8 +21,8 @@
 // stay exact.
 //
 // Down projection with K-split (a property of the context's configuration: weight-streaming shapes
-// have too few output tiles to fill the chip): K is cut into 4 contiguous quarters, each computed by
-// its own workgroup into a partial plane; a second kernel adds the planes in the fixed order
+// have too few output tiles to fill the chip): K is cut into 2 or 4 contiguous ranges, each computed
+// by its own workgroup into a partial plane; a second kernel adds the planes in the fixed order
 // ((p0+p1)+p2)+p3.
 //
 // A launch works on row segments: the host joins the row-adjacent units of one expert in a call (the
@@ -31,7 +31,7 @@
 // that share weight tiles keep the same pace.
 //
 // Determinism.  Each output element is one chain of MFMA accumulations over K in ascending order
-// (K-split: 4 chains added in a fixed order), the same for every row of the context: it depends on
+// (K-split: 2 or 4 chains added in a fixed order), the same for every row of the context: it depends on
 // neither the tile a row sits in, nor the rows that share it, nor the weight layout.  Results are
 // therefore bit-identical however the unit list is split into launches.
 #pragma once
@@ -81,7 +81,7 @@ __device__ __forceinline__ void static_for(F &&f) {
 // Launch-local arguments of the bf16 kernels.
 struct BArgs {
     KArgs k;
-    int ksplit;          // 1, or 4: K quarters, one workgroup each, partial planes in k.dst
+    int ksplit;          // 1, or 2 or 4: K ranges, one workgroup each, partial planes in k.dst
     long plane;          // elements between partial planes
     int nseg;            // > 0: work on seg[0..nseg); 0: on units[u0 .. u0+nu) of the device list
     Seg seg[kMaxSegs];
@@ -420,13 +420,13 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     }
 }
 
-// Workgroup id -> (unit, column tile, K quarter).  The hardware deals consecutive workgroup ids
+// Workgroup id -> (unit, column tile, K range).  The hardware deals consecutive workgroup ids
 // round-robin to the 8 XCDs (each with its own L2).  Work is cut into packets of 4 consecutive
 // units (in launch order) x 8 consecutive column tiles = 32 workgroups = one XCD's 32 CUs: the 4
 // token tiles are each shared by 8 workgroups and, when the units belong to one expert (chunks of
 // a long queue, or its LS and BE part), the 8 weight tiles by up to 4.  Packet q goes to XCD q % 8;
 // the workgroups of a packet get ids 8 apart.  With a K-split the column-tile axis is
-// (quarter, tile), quarter slowest, so a packet stays inside one quarter.
+// (range, tile), range slowest, so a packet stays inside one K range.
 template <bool STREAM>
 __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct, int &kq) {
     const int w = blockIdx.x;
