@@ -201,6 +201,20 @@ __global__ __launch_bounds__(kPermBlock) void perm_fused(const int32_t *__restri
         if (a - n * k == 0) cls[n] = (uint8_t)c;
     }
     __syncthreads();
+    // The report leaves as soon as the histogram is complete: wave 0 writes the counts and the number
+    // of units they imply, fences, and stores the sequence word, while the other waves go on.
+    if (w == 0) {
+        int nu_part = 0;
+        for (int b = l; b < nb; b += 64) {
+            report[b] = tot[b];
+            nu_part += (tot[b] + C - 1) / C;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) nu_part += __shfl_xor(nu_part, o, 64);
+        if (l == 0) report[nb] = nu_part;
+        __threadfence_system();
+        if (l == 0) __hip_atomic_store(report + nb + 1, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     for (int b = tid; b < nb; b += kPermBlock) boff[b] = tot[b];
     __syncthreads();
     const int total = block_excl_scan(boff, tmp, nb);
@@ -213,7 +227,6 @@ __global__ __launch_bounds__(kPermBlock) void perm_fused(const int32_t *__restri
     __syncthreads();
     const int nu = block_excl_scan(ustart, tmp, nb);
     if (tid == 0) *n_units = nu;
-    report_to_host(report, seq, tot, nb, nu);
     for (int q = tid; q < nb; q += kPermBlock) {
         const int cl = q / E, e = q - cl * E;
         const int len = tot[2 * e + cl], first = boff[2 * e + cl];
