@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2031556184, "cfg4": 1920117515, "cfg3_be": 3336284064, "cfg5": 2029952310,
-                          "cfg4_mxfp4": 515872653, "cfg3_be_mxfp4": 1542360123}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2030989674, "cfg4": 1920201172, "cfg3_be": 3279625939, "cfg5": 2093874789,
+                          "cfg4_mxfp4": 516047793, "cfg3_be_mxfp4": 1541557747}
 
 
 def log(*a):
