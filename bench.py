@@ -238,6 +238,8 @@ def serve_bench(args) -> int:
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         return 3
+    from paper_2503_09304_amd.build import ensure_built
+    ensure_built()
     q.lib()
     c = wl.CONFIGS["cfg2"]
     w, keep = serve.synthetic_weights(c.E, c.H, c.F, seed=c.weight_seed or c.seed)
@@ -320,6 +322,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         return 3
+    from paper_2503_09304_amd.build import ensure_built
+    ensure_built()  # what is built is what runs; built here only if there is nothing
     q.lib()  # fail loudly if the HIP library is missing
     cfg = wl.CONFIGS[args.workload]
     es = wl.elem_bytes(cfg)

@@ -52,5 +52,11 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, the smoke run and the benchmark call this; the
+    binding itself never builds and never falls back: it raises when the library is missing)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; they build it only if there is none
+    from paper_2503_09304_amd.build import ensure_built
+    ensure_built()
 
 
 def pytest_collection_modifyitems(config, items):
