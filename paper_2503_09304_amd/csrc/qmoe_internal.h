@@ -86,9 +86,9 @@ struct ExpertArgs {
     const void *S1, *S3, *S2;   // 4-bit weights: block scales
     const Seg *segs;            // host array [nseg] (nseg <= kMaxSegs), or nullptr: use the unit list
     int nseg;
-    int ksplit;                 // 1 or 4 (down projection; fixed per context)
+    int ksplit;                 // 1, 2 or 4 K ranges (down projection; fixed per context)
     int wave_cols;              // bf16 gate-up: columns per wave, 0 = chosen per launch
-    float *partial;             // [4][A][H] fp32 partial planes of the K-split down projection, or nullptr
+    float *partial;             // [ksplit][A][H] fp32 partial planes of the K-split down projection, or nullptr
     long plane;                 // elements per plane
     const int32_t *go;          // gate word of this launch on the device, or nullptr (see launch_gate)
 };
