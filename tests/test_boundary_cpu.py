@@ -89,3 +89,21 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(b, "_LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         b.lib()
+
+
+def test_default_k_split_takes_the_fewest_ranges_that_fill_the_chip():
+    """down_ksplit = 0 is resolved from the configuration alone (include/qmoe.h); the workspace size
+    shows the choice: one partial plane of max_tokens*k*H floats per K range."""
+    def size(E, k, H, F, tokens, ks):
+        return q.moe_workspace_bytes(q.MoeConfig(E, k, H, F, q.MOE_BF16, 256, tokens, ks))
+    # Mixtral shape, decode-sized batch: 8 experts x 16 column tiles x 2 ranges = 256 workgroups
+    assert size(8, 2, 4096, 14336, 64, 0) == size(8, 2, 4096, 14336, 64, 2)
+    assert size(8, 2, 4096, 14336, 64, 2) < size(8, 2, 4096, 14336, 64, 4)
+    assert size(8, 2, 4096, 14336, 64, 1) < size(8, 2, 4096, 14336, 64, 2)
+    # 64 experts x 8 column tiles fill the chip without a split
+    assert size(64, 8, 2048, 1408, 64, 0) == size(64, 8, 2048, 1408, 64, 1)
+    # 4 experts x 4 column tiles: four ranges where F allows them, two where it only allows those
+    assert size(4, 2, 1024, 1024, 64, 0) == size(4, 2, 1024, 1024, 64, 4)
+    assert size(4, 2, 1024, 896, 64, 0) == size(4, 2, 1024, 896, 64, 2)
+    # compute-bound batches (more than 256 rows per expert on average) never split
+    assert size(8, 2, 4096, 14336, 4096, 0) == size(8, 2, 4096, 14336, 4096, 1)
