@@ -239,6 +239,8 @@ class OracleLayer:
         self.units = units(self.cnt, chunk_rows)
         self.next_unit = 0
         self.O: Optional[np.ndarray] = None
+        self.keep_act = False                     # set before running to also keep the activations (self.act [A,F])
+        self.act: Optional[np.ndarray] = None
         self.done = np.zeros(self.N * k, dtype=np.uint8)
         self.executed = np.zeros(len(self.units), dtype=np.int32)
 
@@ -251,7 +253,13 @@ class OracleLayer:
             self.O = np.full((self.N * self.k, self.H), np.nan, dtype=np.float64)
         e, _cls, r0, rows = (int(v) for v in self.units[u])
         toks = self.perm[r0:r0 + rows] // self.k
-        self.O[r0:r0 + rows] = expert_rows(self.x, self.w["W1"], self.w["W3"], self.w["W2"], e, toks)
+        if self.keep_act:
+            if self.act is None:
+                self.act = np.full((self.N * self.k, self.w["W1"].shape[1]), np.nan, dtype=np.float64)
+            self.O[r0:r0 + rows], self.act[r0:r0 + rows] = expert_rows(self.x, self.w["W1"], self.w["W3"], self.w["W2"],
+                                                                         e, toks, want_act=True)
+        else:
+            self.O[r0:r0 + rows] = expert_rows(self.x, self.w["W1"], self.w["W3"], self.w["W2"], e, toks)
         self.done[r0:r0 + rows] = 1
         self.executed[u] += 1
 

@@ -29,3 +29,16 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    # The error figures the GPU parity tests measured (also for tests that passed, whose output pytest
+    # does not show): one line per compared tensor.
+    try:
+        import gpu_util
+    except Exception:  # pragma: no cover
+        return
+    if gpu_util.REPORT:
+        terminalreporter.write_sep("-", "parity figures (GPU vs oracle)")
+        for line in gpu_util.REPORT:
+            terminalreporter.write_line(line)

@@ -1,10 +1,51 @@
-"""Helpers of the GPU tests: the layer object of the package plus error metrics."""
+"""Helpers of the GPU tests: the layer object of the package, error metrics, and the bars a bf16
+result is held to.
+
+The bf16 path performs exactly two roundings the fp64 oracle does not: the SwiGLU activation is
+rounded to bf16 once (it is an MFMA operand) and y is rounded to bf16 once; everything else is fp32
+accumulation, whose error (~1e-6 relative) is negligible beside them.  The bars below follow from
+that, not from observed errors:
+
+  * Rounding a value to bf16 (8 significant bits, nearest even) leaves an error uniform within
+    +-2^(e-8) in the binade [2^e, 2^(e+1)); for values spread smoothly over binades its relative RMS is
+        RHO = 2^-7 * sqrt(E[m^-2] / 12) = 2^-7 * sqrt((3/8) / (12 ln 2)) = 1.659e-3
+    (m the mantissa in [1,2), log-uniform).  test_tolerance_model.py checks this figure on the CPU.
+  * An expert output is out[r,h] = sum_f W2[h,f] act[r,f].  The rounding error of act[r,f] is uniform
+    within half an ulp of it, variance ulp(act[r,f])^2 / 12, independent from element to element, so
+        SIGMA[r,h]^2 = sum_f W2[h,f]^2 * ulp(act[r,f])^2 / 12.
+    The tests compute exactly this from the activations the oracle keeps (sigma_out_exact; the
+    product runs in fp32, which is ample for a standard deviation).  Averaged over weights
+    independent of the activations it is RHO * RMS_h(out[r,:]); single elements lie up to 2x above
+    that average, which is why the per-element form is used.
+  * y[n,:] = sum_j w_j out[row_j,:] inherits sqrt(sum_j w_j^2 SIGMA_j^2) before its own rounding, which
+    adds at most half an ulp of the value being rounded.
+
+Per element:  |out - ref| <= C_SIGMA * SIGMA,   |y - ref| <= C_SIGMA * SIGMA_Y + half_ulp(|ref| + C_SIGMA * SIGMA_Y)
+with C_SIGMA = 8 (the largest of 1e8 Gaussian errors is about 6 sigma).  The global bar of the bf16
+workloads, max|err| / RMS(ref) <= 2e-2, is asserted on everything the path computes in fp32: the
+expert outputs and y before its rounding (moe_combine with MOE_Y_F32); the stored bf16 y must be,
+bit for bit, that fp32 y rounded once to nearest-even.  For the bf16 y itself the global figure is
+printed: at the full sizes rounding the oracle's exact y to bf16 already costs 1.6e-2 to 2.2e-2 of
+RMS (the largest outputs sit 4 to 8 RMS out, where half an ulp is 1.6e-2 to 3.1e-2 of RMS).  Over all elements: rms(err)/RMS(ref) must stay near
+RHO for the expert outputs (gate 1.35 * RHO) and near sqrt(2) * RHO for y, which is rounded a second
+time (gate 1.3 * sqrt(2) * RHO); an additional systematic kernel error of 2e-3 RMS breaks
+either gate, however well it hides under the largest outputs' final rounding.
+"""
 from __future__ import annotations
+
+import math
 
 import numpy as np
 
 import workloads as wl
 from paper_2503_09304_amd.layer import DEV, DevWeights, DevWeightsMX, GpuLayer, to_dev, to_host  # noqa: F401
+
+RHO = 2.0 ** -7 * math.sqrt((3.0 / 8.0) / (12.0 * math.log(2.0)))    # 1.659e-3
+C_SIGMA = 8.0
+RMS_GATE_OUT = 1.35 * RHO                        # 2.24e-3
+RMS_GATE_Y = 1.3 * math.sqrt(2.0) * RHO          # 3.05e-3
+REPORT: list = []                                # lines the terminal summary prints (conftest.py)
+MIN_ELEMS_FOR_RMS_GATE = 4096                    # below this an RMS over the elements is too noisy an estimate
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
@@ -15,18 +56,115 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(got - ref)) / rms) if ref.size else 0.0
 
 
-def bf16_y_tol(y_ref: np.ndarray, before_rounding: float = 1.2e-2, bar: float = 2e-2) -> float:
-    """Bar for a bf16 y outside the named configurations (4-bit weights, small random shapes), where
-    the final rounding alone can take most of 2e-2: the error before the final rounding (budget
-    1.2e-2 of RMS: activation rounding to bf16, fp32 accumulation) plus the most that rounding can
-    add, half an ulp in the binade of the largest |y| (2^-8 of that power of two); never below the
-    2e-2 of the named configurations."""
-    y = np.abs(np.asarray(y_ref, dtype=np.float64))
-    rms = float(np.sqrt(np.mean(y * y))) if y.size else 0.0
-    if rms == 0.0:
-        return bar
-    half_ulp = 2.0 ** (np.floor(np.log2(y.max())) - 8)
-    return max(bar, before_rounding + half_ulp / rms)
+def half_ulp_bf16(v: np.ndarray) -> np.ndarray:
+    """Half a unit in the last place of bf16 at magnitude v: 2^(floor(log2 v) - 8); 0 at 0."""
+    v = np.abs(np.asarray(v, dtype=np.float64))
+    out = np.zeros_like(v)
+    nz = v > 0
+    out[nz] = np.exp2(np.floor(np.log2(v[nz])) - 8.0)
+    return out
+
+
+def row_rms(a: np.ndarray) -> np.ndarray:
+    a = np.asarray(a, dtype=np.float64)
+    return np.sqrt(np.mean(a * a, axis=1))
+
+
+def _blocks(n: int, width: int, budget: int = 1 << 24):
+    step = max(1, budget // max(width, 1))
+    for i in range(0, n, step):
+        yield slice(i, min(n, i + step))
+
+
+def ulp_bf16(v: np.ndarray) -> np.ndarray:
+    return 2.0 * half_ulp_bf16(v)
+
+
+def sigma_out_exact(act_ref: np.ndarray, w2: np.ndarray) -> np.ndarray:
+    """SIGMA[r,h] of the rows of one expert: act_ref [rows,F] (the oracle's, fp64), w2 [H,F] (fp64).
+    Scaled to order one and multiplied in fp32."""
+    u = ulp_bf16(act_ref)
+    su, sw = float(u.max()) or 1.0, float(np.abs(w2).max()) or 1.0
+    var = ((u / su) ** 2).astype(np.float32) @ ((w2 / sw) ** 2).astype(np.float32).T
+    return np.sqrt(var.astype(np.float64) / 12.0) * (su * sw)
+
+
+def sigma_out_layer(lay, w2_of) -> np.ndarray:
+    """SIGMA [A,H] of a whole oracle layer that was run with keep_act set; w2_of(e) -> W2[e] as fp64 [H,F]."""
+    sigma = np.zeros_like(lay.O)
+    for e in range(lay.E):
+        r0, r1 = int(lay.off[2 * e]), int(lay.off[2 * e + 2])
+        if r1 > r0:
+            sigma[r0:r1] = sigma_out_exact(lay.act[r0:r1], w2_of(e))
+    return sigma
+
+
+def check_bf16_expert_out(out_gpu: np.ndarray, out_ref: np.ndarray, sigma: np.ndarray) -> dict:
+    """fp32 results of the bf16 path (the expert outputs with sigma [A,H] from sigma_out_layer, or the
+    unrounded y with sigma [N,H] from sigma_y) against the oracle's, every element.  Returns the
+    figures; `ok` says whether the global 2e-2 bar, the per-element bar and the RMS gate all hold."""
+    A, H = out_ref.shape
+    se = sr = 0.0
+    mx = worst = 0.0
+    for s in _blocks(A, H):
+        ref = np.asarray(out_ref[s], dtype=np.float64)
+        err = np.abs(np.asarray(out_gpu[s], dtype=np.float64) - ref)
+        sig = sigma[s]
+        se += float(np.sum(err * err)); sr += float(np.sum(ref * ref))
+        mx = max(mx, float(err.max()))
+        with np.errstate(divide="ignore", invalid="ignore"):
+            ratio = np.where(sig > 0, err / (C_SIGMA * sig), np.where(err > 0, np.inf, 0.0))
+        worst = max(worst, float(ratio.max()))
+    n = A * H
+    rms = math.sqrt(sr / n) if n else 0.0
+    res = {"max_rel": mx / rms if rms else 0.0, "rms_rel": math.sqrt(se / n) / rms if rms else 0.0,
+           "worst_over_bar": worst, "elems": n}
+    res["ok"] = (res["max_rel"] <= 2e-2 and worst <= 1.0 and
+                 (n < MIN_ELEMS_FOR_RMS_GATE or res["rms_rel"] <= RMS_GATE_OUT))
+    return res
+
+
+def sigma_y(wt: np.ndarray, inv: np.ndarray, sigma: np.ndarray) -> np.ndarray:
+    """SIGMA_Y [N,H] = sqrt(sum_j w_j^2 SIGMA[inv[n*k+j]]^2)."""
+    N, k = wt.shape
+    pos = np.asarray(inv).reshape(N, k)
+    w = np.asarray(wt, dtype=np.float64)
+    acc = np.zeros((N, sigma.shape[1]))
+    for j in range(k):
+        acc += (w[:, j][:, None] * sigma[pos[:, j]]) ** 2
+    return np.sqrt(acc)
+
+
+def check_bf16_y(y_gpu: np.ndarray, y_ref: np.ndarray, sig_y: np.ndarray, need_global: bool = False) -> dict:
+    """y as stored in bf16 (given here as exact fp64 values) against the oracle's, every element: the
+    per-element bar with its half ulp, and the RMS gate.  The global max|err|/RMS is reported; it is
+    part of `ok` only with need_global (rounding the exact y to bf16 can by itself cost more than
+    2e-2 of RMS at the largest outputs, so the global bar is asserted on the unrounded fp32 y instead)."""
+    N, H = y_ref.shape
+    se = sr = 0.0
+    mx = worst = 0.0
+    for s in _blocks(N, H):
+        ref = np.asarray(y_ref[s], dtype=np.float64)
+        err = np.abs(np.asarray(y_gpu[s], dtype=np.float64) - ref)
+        pre = C_SIGMA * sig_y[s]
+        bar = pre + half_ulp_bf16(np.abs(ref) + pre)
+        se += float(np.sum(err * err)); sr += float(np.sum(ref * ref))
+        mx = max(mx, float(err.max()))
+        with np.errstate(divide="ignore", invalid="ignore"):
+            ratio = np.where(bar > 0, err / bar, np.where(err > 0, np.inf, 0.0))
+        worst = max(worst, float(ratio.max()))
+    n = N * H
+    rms = math.sqrt(sr / n) if n else 0.0
+    res = {"max_rel": mx / rms if rms else 0.0, "rms_rel": math.sqrt(se / n) / rms if rms else 0.0,
+           "worst_over_bar": worst, "elems": n}
+    res["ok"] = ((not need_global or res["max_rel"] <= 2e-2) and worst <= 1.0 and
+                 (n < MIN_ELEMS_FOR_RMS_GATE or res["rms_rel"] <= RMS_GATE_Y))
+    return res
+
+
+def fmt(res: dict) -> str:
+    return (f"max|err|/RMS {res['max_rel']:.3e}  rms(err)/RMS {res['rms_rel']:.3e}  "
+            f"worst element at {res['worst_over_bar']:.2f} of its bar  ({res['elems']} elements)")
 
 
 def as_f64(a: np.ndarray) -> np.ndarray:

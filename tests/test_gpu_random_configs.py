@@ -9,7 +9,8 @@ import torch
 import oracle
 import paper_2503_09304_amd as q
 import workloads as wl
-from gpu_util import DevWeights, GpuLayer, bf16_y_tol, rel_err
+from gpu_util import DevWeights, GpuLayer, rel_err
+from test_gpu_parity import check_values
 
 pytestmark = pytest.mark.gpu
 
@@ -41,20 +42,15 @@ def test_random_configuration(case):
     inp = wl.make_inputs(cfg)
     dw = DevWeights(inp.w).packed() if packed else DevWeights(inp.w)
     g = GpuLayer(inp, dw, down_ksplit=ks).full()
-    r = g.fetch("logits", "topk_idx", "counts", "perm", "inv", "expert_out", "y")
+    r = g.fetch("logits", "topk_idx", "counts", "perm", "inv", "y")
     assert rel_err(r["logits"], oracle.gate_logits(inp.x, inp.w["Wg"], inp.bias)) <= 2e-5
     # the oracle's selection replayed on the kernel's fp32 logits, and everything downstream of it
     lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows, logits=r["logits"].astype(np.float64))
     assert np.array_equal(r["topk_idx"], lay.idx) and np.array_equal(r["counts"], lay.cnt)
     assert np.array_equal(r["perm"], lay.perm) and np.array_equal(r["inv"], lay.inv)
     assert [tuple(int(v) for v in u) for u in oracle.units(lay.cnt, cfg.chunk_rows)] == g.ctx.units()
-    lay.run()
-    y_ref, comp = lay.y()
-    assert comp.all()
+    check_values(cfg, lay, g, r["y"])
     bf = cfg.dtype == "bf16"
-    tol = 2e-2 if bf else 1e-4
-    assert rel_err(r["expert_out"], lay.O) <= tol
-    assert rel_err(wl.as_f64(r["y"]), y_ref) <= (bf16_y_tol(y_ref) if bf else tol)
     nu = g.ctx.cursor.n_units
     if nu > 1:
         cuts = tuple(sorted(set(int(c) for c in rng.integers(1, nu, size=min(4, nu - 1)))))

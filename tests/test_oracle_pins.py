@@ -424,3 +424,20 @@ def test_workload_recipes():
     w = wl.make_weights(wl.scaled(c5, E=2, F=64, H=128))
     assert abs(float(wl.bf16_bits_to_f32(w["W1"]).std()) - 0.02) < 1e-3
     assert w["W1"].shape == (2, 64, 128) and w["W2"].shape == (2, 128, 64) and w["Wg"].shape == (128, 2)
+
+
+def test_kept_activations_are_the_swiglu_values_and_leave_the_outputs_alone():
+    """OracleLayer.keep_act stores silu(W1 x) * (W3 x) per sorted row (used by the GPU tests to size
+    the error of the bf16 path's activation rounding); the outputs are the same with and without."""
+    cfg = small_cfg(seed=91, N=30, k=3)
+    inp = wl.make_inputs(cfg)
+    a = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    b = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows)
+    b.keep_act = True
+    a.run(); b.run(3); b.run()
+    assert a.act is None and np.array_equal(a.O, b.O)
+    x = wl.as_f64(inp.x)
+    for r in range(cfg.A):
+        n, e = b.perm[r] // cfg.k, b.idx.reshape(-1)[b.perm[r]]
+        want = np_silu(wl.as_f64(inp.w["W1"][e]) @ x[n]) * (wl.as_f64(inp.w["W3"][e]) @ x[n])
+        np.testing.assert_allclose(b.act[r], want, rtol=1e-12, atol=1e-15)
