@@ -129,7 +129,8 @@ typedef struct {
     int32_t rows; /* 1..chunk_rows */
 } moe_unit;
 
-enum { MOE_CLASS_LS = 1, MOE_CLASS_BE = 2, MOE_CLASS_ALL = 3 };
+enum { MOE_CLASS_LS = 1, MOE_CLASS_BE = 2, MOE_CLASS_ALL = 3,
+       MOE_Y_F32 = 4 /* moe_combine: or-ed into class_mask, y is float [n_tokens,H] whatever the context's dtype */ };
 
 typedef enum {
     MOE_GET_LOGITS = 0,     /* float   [N,E]    router logits (bias included)                   */
@@ -157,7 +158,10 @@ size_t moe_workspace_bytes(const moe_config *cfg);
  * instead of the width the launch would pick; results do not depend on it). */
 int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_bytes, moe_ctx **out);
 
-/* Frees the host object (and its pinned buffer).  Does not wait for enqueued work. */
+/* Frees the host object (and its pinned buffer).  Does not wait for enqueued work: the caller makes
+ * sure that nothing of this context is still on a stream.  Between moe_expert_enqueue and
+ * moe_expert_collect the kernels of the sequence read and write the pinned buffer, so the call is
+ * refused with MOE_E_STATE (nothing is freed): collect first. */
 int32_t moe_destroy(moe_ctx *ctx);
 
 /* One-time re-layout of the weights at model load (outside any timed region).  src: row-major
@@ -168,7 +172,7 @@ int32_t moe_destroy(moe_ctx *ctx);
  * bf16 layout.  cfg->dtype must be MOE_BF16 (MOE_E_ARG otherwise).  Enqueues on `stream` and returns. */
 int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weights *dst, void *stream);
 
-/* Router (Sec. 2.1: "a router that assigns each token to the most relevant experts"; Sec. 2.2).
+/* Router (Sec. 2.1 and 2.2).
  *   logits[n,e] = sum_h x[n,h]*Wg[h,e] + logit_bias[e]      (fp32 accumulation)
  *   slot j of token n = j-th expert in the order (logit descending, expert index ascending)
  *   w[n,j] = exp(l_j - l_0) / sum_{i<k} exp(l_i - l_0)      (softmax renormalised over the k)
@@ -199,6 +203,13 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
  * the tensors given to moe_route, unchanged.  *cursor must be the value last returned for this
  * context (MOE_E_ARG otherwise): no unit is ever executed twice.  Results do not depend on how
  * the unit list is split into calls, bit for bit.
+ * Order on the device: list order holds from call to call (everything one call enqueues runs before
+ * what the next call enqueues).  Inside one call the bf16 kernels take the call's units expert by
+ * expert, so that an expert's LS and BE rows share one pass over its weights: a call that spans both
+ * phases finishes its LS rows with the rest.  A caller that wants the LS rows out first cuts the
+ * call at the end of the LS phase (the units with cls == 0 come first in the list: moe_units), runs
+ * moe_combine(MOE_CLASS_LS), then carries on; that costs a second pass over the weights of every
+ * expert that holds rows of both classes.
  * Returns MOE_OK while units remain, MOE_DONE when every unit has run. */
 int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t max_units,
                        moe_cursor *cursor, void *stream);
@@ -206,15 +217,16 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
 /* Expert work in an order the caller chooses (Sec. 3.1 "User-defined scheduling policies", Sec. 3.2:
  * policies at the granularity of experts, e.g. selective expert execution).  unit_ids [host]
  * uint32[n]: indices into the context's unit list (moe_units), distinct, each not yet executed; any
- * order.  The arithmetic per row is that of moe_expert_run, bit for bit.  On a bad id (out of range,
+ * order (honoured from call to call; inside one call the device takes the units expert by expert, see
+ * moe_expert_run).  The arithmetic per row is that of moe_expert_run, bit for bit.  On a bad id (out of range,
  * repeated, already executed) nothing runs and MOE_E_ARG is returned.  *cursor ([host], may be
  * NULL) receives the context's cursor afterwards: next_unit = first unit that has not run, so
  * moe_expert_run can carry on from it.  Returns MOE_OK while units remain, MOE_DONE when all ran. */
 int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, const uint32_t *unit_ids,
                              uint32_t n, moe_cursor *cursor, void *stream);
 
-/* Expert work enqueued ahead and stopped from the device side (Sec. 5 "Overlapping preemption with execution":
- * named there as future work).  moe_expert_enqueue puts ALL units that have
+/* Expert work enqueued ahead and stopped from the device side (Discussion, Sec. 6, paragraph on
+ * overlapping preemption with execution: named there as future work).  moe_expert_enqueue puts ALL units that have
  * not run yet on the stream, as launches of units_per_launch units each, and returns without waiting.
  * In front of every launch a one-thread gate kernel reads the context's stop word (host memory mapped
  * into the device): while it is clear the launch runs in full; once it is set, that launch and every
@@ -239,7 +251,10 @@ int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream);
  * accumulated in fp32 from zero in that fixed order, rounded once to the output type.
  * class_mask selects which tokens' rows of y ([device] [n_tokens,H]) are written: MOE_CLASS_LS,
  * MOE_CLASS_BE or MOE_CLASS_ALL; rows of other tokens are left untouched.  If a selected class
- * still has unexecuted units the call fails with MOE_E_INCOMPLETE. */
+ * still has unexecuted units the call fails with MOE_E_INCOMPLETE.  With MOE_Y_F32 or-ed in, y is
+ * float and receives the fp32 sums unrounded: for a bf16 context the bf16 y is exactly that value
+ * rounded once to nearest-even, so the flag shows a caller (and the tests) the result before the
+ * one rounding the output type costs. */
 int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream);
 
 /* Combine of whatever is complete (Sec. 3.1 "Top-k expert selection": fully and partially processed
@@ -251,7 +266,12 @@ int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream);
 int32_t moe_combine_complete(moe_ctx *ctx, void *y, uint8_t *complete, void *stream);
 
 /* Read-back for tests and schedulers: a [device] pointer into the workspace and its size in bytes
- * for the current layer-batch.  Valid until the next moe_route on this context. */
+ * for the current layer-batch.  Valid until the next moe_route on this context.
+ * MOE_GET_EXPERT_OUT on a context whose down projection is K-split (down_ksplit, chosen or implied):
+ * the kernels keep the K ranges' partial sums apart and moe_combine adds them as it reads them, so
+ * this request first enqueues, on the stream of the context's last expert launch, a kernel that adds
+ * them ((p0+p1)+p2)+p3 into the returned array for the rows executed so far: read it in stream order
+ * or after synchronising. */
 int32_t moe_get(moe_ctx *ctx, int32_t what, const void **dev_ptr, size_t *bytes);
 
 /* Host copy of the context's work-unit list (after moe_permute).  Writes at most `cap` entries to
@@ -270,7 +290,8 @@ int32_t moe_plan_units(const int32_t *cnt, int32_t E, int32_t chunk_rows, moe_un
  * microseconds of stream time.  moe_profile_read waits for the recorded events, adds up elapsed
  * milliseconds and launch counts per kernel kind since the last read into ms / launches ([host],
  * MOE_PROF_KINDS entries each) and forgets them. */
-enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2, MOE_PROF_KINDS = 3, MOE_PROF_ALL = 7 };
+enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2 /* unused: no such launch any more */,
+       MOE_PROF_KINDS = 3, MOE_PROF_ALL = 7 };
 int32_t moe_profile(moe_ctx *ctx, int32_t kinds);
 int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches);
 

@@ -16,6 +16,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_OK, MOE_DONE = 0, 1
 MOE_E_ARG, MOE_E_STATE, MOE_E_INCOMPLETE, MOE_E_WORKSPACE, MOE_E_HIP = -1, -2, -3, -4, -5
 MOE_CLASS_LS, MOE_CLASS_BE, MOE_CLASS_ALL = 1, 2, 3
+MOE_Y_F32 = 4
 MOE_W_ROWMAJOR, MOE_W_PACKED, MOE_W_MXFP4_ROWMAJOR, MOE_W_MXFP4 = 0, 1, 2, 3
 UINT32_MAX = 0xFFFFFFFF
 
@@ -178,8 +179,13 @@ class Context:
         self._w = None
 
     def close(self):
+        """Destroys the context.  If a launch sequence is still enqueued (moe_destroy refuses then: its
+        kernels use the context's pinned buffer) it is collected first, which waits for the stream."""
         if getattr(self, "h", None):
-            lib().moe_destroy(self.h)
+            if lib().moe_destroy(self.h) == MOE_E_STATE:
+                cur = MoeCursor(0, 0)
+                lib().moe_expert_collect(self.h, C.byref(cur), _stream())
+                lib().moe_destroy(self.h)
             self.h = None
 
     def __del__(self):

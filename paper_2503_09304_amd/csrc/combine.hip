@@ -14,11 +14,27 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// One 16-byte piece of an expert output row.  KS > 1: the down projection left KS partial planes
+// (K ranges); they are added here in the fixed order ((p0 + p1) + p2) + p3, so the value is the one a
+// separate reduction pass would have stored.  Read once: non-temporal.
+template <int KS>
+__device__ __forceinline__ f32x4 load_out(const float *__restrict__ p, long plane) {
+    f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    if constexpr (KS > 1) {
+#pragma unroll
+        for (int q = 1; q < KS; ++q) {
+            const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p + q * plane));
+            v[0] = v[0] + t[0]; v[1] = v[1] + t[1]; v[2] = v[2] + t[2]; v[3] = v[3] + t[3];
+        }
+    }
+    return v;
+}
+
 // done == nullptr: tokens are selected by class (the host has checked that the class is finished).
 // done != nullptr: a token is selected when done[] is set for all k of its sorted positions;
 // complete[n] (if given) reports the selection.
-template <bool BF16>
-__global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ out, const float *__restrict__ topk_w,
+template <bool BF16, int KS>
+__global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ out, long plane, const float *__restrict__ topk_w,
                                                     const int32_t *__restrict__ inv, const uint8_t *__restrict__ cls,
                                                     const uint8_t *__restrict__ done, uint8_t *__restrict__ complete,
                                                     void *__restrict__ y, int N, int H, int k, int class_mask) {
@@ -48,7 +64,7 @@ __global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ ou
         for (int h = threadIdx.x * 4; h < H; h += 1024) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int j = 0; j < k; ++j) {
-                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(out + (long)sp[j] * H + h));   // read once
+                const f32x4 v = load_out<KS>(out + (long)sp[j] * H + h, plane);
                 const float wj = sw[j];
                 acc.x = fmaf(wj, v.x, acc.x);
                 acc.y = fmaf(wj, v.y, acc.y);
@@ -65,7 +81,12 @@ __global__ __launch_bounds__(256) void combine_rows(const float *__restrict__ ou
     } else {
         for (int h = threadIdx.x; h < H; h += 256) {
             float acc = 0.f;
-            for (int j = 0; j < k; ++j) acc = fmaf(sw[j], out[(long)sp[j] * H + h], acc);
+            for (int j = 0; j < k; ++j) {
+                float v = out[(long)sp[j] * H + h];
+#pragma unroll
+                for (int q = 1; q < KS; ++q) v = v + out[q * plane + (long)sp[j] * H + h];
+                acc = fmaf(sw[j], v, acc);
+            }
             if (BF16) ((__bf16 *)y)[(long)n * H + h] = (__bf16)acc;
             else ((float *)y)[(long)n * H + h] = acc;
         }
@@ -107,14 +128,18 @@ hipError_t launch_gate(const int32_t *stop_host, int32_t *completed_host, int32_
     return hipGetLastError();
 }
 
+template <bool BF16, int KS>
+static void launch_combine_ks(const CombineArgs &a, hipStream_t s) {
+    hipLaunchKernelGGL((combine_rows<BF16, KS>), dim3(a.N), dim3(256), 0, s, a.out, a.plane, a.topk_w, a.inv, a.cls, a.done,
+                       a.complete, a.y, a.N, a.H, a.k, a.class_mask);
+}
+
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s) {
     if (a.N <= 0) return hipSuccess;
-    if (a.dtype == MOE_BF16)
-        hipLaunchKernelGGL(combine_rows<true>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.done,
-                           a.complete, a.y, a.N, a.H, a.k, a.class_mask);
-    else
-        hipLaunchKernelGGL(combine_rows<false>, dim3(a.N), dim3(256), 0, s, a.out, a.topk_w, a.inv, a.cls, a.done,
-                           a.complete, a.y, a.N, a.H, a.k, a.class_mask);
+    const bool bf = a.dtype == MOE_BF16;
+    if (a.ksplit == 4) { if (bf) launch_combine_ks<true, 4>(a, s); else launch_combine_ks<false, 4>(a, s); }
+    else if (a.ksplit == 2) { if (bf) launch_combine_ks<true, 2>(a, s); else launch_combine_ks<false, 2>(a, s); }
+    else { if (bf) launch_combine_ks<true, 1>(a, s); else launch_combine_ks<false, 1>(a, s); }
     return hipGetLastError();
 }
 

@@ -10,24 +10,22 @@ namespace {
 using bf16k::BArgs;
 using bf16k::f32x4;
 
-// out[r,:] = ((p0 + p1) + p2) + p3 (or p0 + p1 with two planes) for the rows of the launch.
-__global__ __launch_bounds__(256) void reduce_planes(const BArgs b, const float *__restrict__ part, float *__restrict__ out, int H) {
-    if (b.k.go != nullptr && *b.k.go == 0) return;
-    const long plane = b.plane;
-    moe_unit un;
-    if (b.nseg > 0) {
-        const Seg g = b.seg[blockIdx.y];
-        un.row0 = (int)g.row0; un.rows = g.rows;
-    } else {
-        un = b.k.units[b.k.u0 + blockIdx.y];
-    }
+// out[r,:] = ((p0 + p1) + p2) + p3 (or p0 + p1 with two planes) for the rows of the segments.
+struct ReduceArgs {
+    int nseg;
+    Seg seg[kMaxSegs];
+};
+
+__global__ __launch_bounds__(256) void reduce_planes(const ReduceArgs b, const float *__restrict__ part, float *__restrict__ out,
+                                                     int H, int ksplit, long plane) {
+    const Seg g = b.seg[blockIdx.y];
     const int per_row = H >> 2;
-    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < (long)un.rows * per_row; i += (long)gridDim.x * 256) {
-        const long off = ((long)un.row0 * H) + i * 4;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < (long)g.rows * per_row; i += (long)gridDim.x * 256) {
+        const long off = ((long)g.row0 * H) + i * 4;
         const f32x4 a = *reinterpret_cast<const f32x4 *>(part + off);
         const f32x4 p1 = *reinterpret_cast<const f32x4 *>(part + plane + off);
         f32x4 v;
-        if (b.ksplit == 4) {
+        if (ksplit == 4) {
             const f32x4 p2 = *reinterpret_cast<const f32x4 *>(part + 2 * plane + off);
             const f32x4 p3 = *reinterpret_cast<const f32x4 *>(part + 3 * plane + off);
 #pragma unroll
@@ -85,6 +83,21 @@ __global__ __launch_bounds__(256) void pack_weights_mxfp4(const uint8_t *__restr
 }
 
 }  // namespace
+
+hipError_t launch_reduce_planes(const Seg *segs, int nseg, const float *partial, float *out, int H, int ksplit, long plane,
+                                hipStream_t s) {
+    for (int i = 0; i < nseg; i += kMaxSegs) {
+        ReduceArgs r{};
+        r.nseg = std::min(kMaxSegs, nseg - i);
+        int max_rows = 1;
+        for (int j = 0; j < r.nseg; ++j) { r.seg[j] = segs[i + j]; max_rows = std::max(max_rows, (int)segs[i + j].rows); }
+        const int per_seg = std::max(1, std::min(64, (max_rows * (H / 4) + 255) / 256));
+        hipLaunchKernelGGL(reduce_planes, dim3(per_seg, r.nseg), dim3(256), 0, s, r, partial, out, H, ksplit, plane);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 
 hipError_t launch_pack_mxfp4(const void *codes, const void *scales, void *dcodes, void *dscales, int E, int R, int K,
                              hipStream_t s) {
@@ -194,10 +207,9 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
         b.ksplit = a.ksplit;
         b.plane = a.plane;
         b.k.dst = a.partial;
-        { Scope sc(a.prof, MOE_PROF_DOWN, s); launch(false); }
-        const int per_seg = std::max(1, std::min(64, (a.max_rows * (a.H / 4) + 255) / 256));
-        Scope sc(a.prof, MOE_PROF_DOWN_REDUCE, s);
-        hipLaunchKernelGGL(reduce_planes, dim3(per_seg, n), dim3(256), 0, s, b, (const float *)a.partial, a.out, a.H);
+        // the planes stay apart: moe_combine adds them in the fixed order ((p0+p1)+p2)+p3 as it reads them
+        Scope sc(a.prof, MOE_PROF_DOWN, s);
+        launch(false);
     } else {
         Scope sc(a.prof, MOE_PROF_DOWN, s);
         launch(false);

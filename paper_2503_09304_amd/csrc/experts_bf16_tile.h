@@ -59,7 +59,10 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
+// silu(z) = z / (1 + e^-z) as one exponential and one reciprocal (v_exp_f32, v_rcp_f32: about 1 ulp
+// each, far below the bf16 rounding the product gets next).  An IEEE division costs three times the
+// instructions, and a workgroup's epilogue applies this to T*32 x 128 values while its MFMA pipes idle.
+__device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
 
 // LDS layout of the token tile: rows of 128 bytes = 8 slots of 16 bytes; slot s of row r is stored
 // at slot s ^ swz(r).  swz is a permutation of 0..7 over any 8 consecutive rows, and over 16

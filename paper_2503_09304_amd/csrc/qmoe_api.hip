@@ -114,6 +114,16 @@ enum State { ST_CREATED = 0, ST_ROUTED = 1, ST_PERMUTED = 2 };
 
 }  // namespace
 
+namespace qmoe {
+int32_t set_error(int32_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+}  // namespace qmoe
+
 struct moe_ctx {
     moe_config cfg;
     Layout lay;
@@ -125,6 +135,8 @@ struct moe_ctx {
     std::vector<moe_unit> units;
     std::vector<uint8_t> executed;             // per unit
     std::vector<uint32_t> unmarked;            // executed units whose rows are not yet flagged on the device
+    std::vector<uint32_t> unreduced;           // K-split contexts: executed units whose partial planes have not been added into `out`
+    hipStream_t last_stream;                   // stream of the last expert launch (moe_get adds the planes there)
     bool done_valid;                           // the device flags of this layer-batch have been cleared
     bool pending;                              // an enqueued launch sequence has not been collected yet
     std::vector<std::vector<uint32_t>> plan;   // the units of each launch of that sequence
@@ -237,6 +249,7 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
     c->next_unit = c->n_units = c->n_ls_units = c->n_done = c->n_ls_done = 0;
     c->done_valid = false;
     c->pending = false;
+    c->last_stream = nullptr;
     c->pinned = nullptr;
     c->pinned_dev = nullptr;
     c->seq = 0;
@@ -259,6 +272,9 @@ int32_t moe_create(const moe_config *cfg, void *workspace, size_t workspace_byte
 
 int32_t moe_destroy(moe_ctx *ctx) {
     if (!ctx) return fail(MOE_E_ARG, "moe_destroy: null context");
+    // the gate kernels of an enqueued sequence read the stop word and store the completed count in
+    // the pinned buffer: it must not be freed under them
+    if (ctx->pending) return fail(MOE_E_STATE, "moe_destroy: an enqueued launch sequence is pending; call moe_expert_collect first");
     if (ctx->pinned) (void)hipHostFree(ctx->pinned);
     for (auto &sp : ctx->prof.spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (auto e : ctx->prof.pool) (void)hipEventDestroy(e);
@@ -310,6 +326,7 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     ctx->units.clear();
     ctx->executed.clear();
     ctx->unmarked.clear();
+    ctx->unreduced.clear();
     ctx->done_valid = false;
     ctx->cnt.assign(2 * (size_t)ctx->cfg.E, 0);
     return MOE_OK;
@@ -381,6 +398,7 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
     ctx->n_done = ctx->n_ls_done = 0;
     ctx->executed.assign(n, 0);
     ctx->unmarked.clear();
+    ctx->unreduced.clear();
     ctx->done_valid = false;
     ctx->state = ST_PERMUTED;
     cursor->next_unit = 0;
@@ -393,6 +411,7 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
 static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
                                 const int32_t *go, hipStream_t stream, const char *who) {
     if (ids.empty()) return MOE_OK;
+    ctx->last_stream = stream;
     qmoe::ExpertArgs a{};
     a.go = go;
     a.x = x; a.W1 = w->W1; a.W3 = w->W3; a.W2 = w->W2;
@@ -489,6 +508,7 @@ static void book_units(moe_ctx *ctx, const std::vector<uint32_t> &ids) {
         ctx->n_done += 1;
         ctx->n_ls_done += ctx->units[i].cls == 0;
         ctx->unmarked.push_back(i);
+        if (ctx->lay.has_partial) ctx->unreduced.push_back(i);
     }
     while (ctx->next_unit < ctx->n_units && ctx->executed[ctx->next_unit]) ++ctx->next_unit;
 }
@@ -612,11 +632,27 @@ int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream) {
     return ctx->n_done == ctx->n_units ? MOE_DONE : MOE_OK;
 }
 
+// Where the combine reads the expert outputs: `out`, or, on a context with a K-split down projection,
+// the partial planes, which it adds as it reads them.
+static void fill_out_source(moe_ctx *ctx, qmoe::CombineArgs &a) {
+    if (ctx->lay.has_partial) {
+        a.out = at<float>(ctx, ctx->lay.partial);
+        a.ksplit = ctx->lay.ksplit;
+        a.plane = (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H;
+    } else {
+        a.out = at<float>(ctx, ctx->lay.out);
+        a.ksplit = 1;
+        a.plane = 0;
+    }
+}
+
 int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
     if (!ctx) return fail(MOE_E_ARG, "moe_combine: null context");
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_combine: call moe_permute first");
     if (ctx->pending) return fail(MOE_E_STATE, "moe_combine: an enqueued launch sequence is pending; call moe_expert_collect first");
-    if (class_mask < 1 || class_mask > 3) return fail(MOE_E_ARG, "moe_combine: class_mask must be 1, 2 or 3");
+    const bool y_f32 = (class_mask & MOE_Y_F32) != 0;
+    class_mask &= ~MOE_Y_F32;
+    if (class_mask < 1 || class_mask > 3) return fail(MOE_E_ARG, "moe_combine: class_mask must be 1, 2 or 3 (optionally | MOE_Y_F32)");
     if (ctx->N > 0 && !y) return fail(MOE_E_ARG, "moe_combine: null y");
     const uint32_t ls_left = ctx->n_ls_units - ctx->n_ls_done;
     const uint32_t be_left = (ctx->n_units - ctx->n_ls_units) - (ctx->n_done - ctx->n_ls_done);
@@ -626,12 +662,12 @@ int32_t moe_combine(moe_ctx *ctx, void *y, int32_t class_mask, void *stream) {
         return fail(MOE_E_INCOMPLETE, "moe_combine: BE tokens still have %u unexecuted units", be_left);
     if (ctx->N == 0) return MOE_OK;
     qmoe::CombineArgs a{};
-    a.out = at<float>(ctx, ctx->lay.out);
+    fill_out_source(ctx, a);
     a.topk_w = at<float>(ctx, ctx->lay.topk_w);
     a.inv = at<int32_t>(ctx, ctx->lay.inv);
     a.cls = at<uint8_t>(ctx, ctx->lay.cls);
     a.y = y;
-    a.N = ctx->N; a.H = ctx->cfg.H; a.k = ctx->cfg.k; a.dtype = ctx->cfg.dtype; a.class_mask = class_mask;
+    a.N = ctx->N; a.H = ctx->cfg.H; a.k = ctx->cfg.k; a.dtype = y_f32 ? MOE_F32 : ctx->cfg.dtype; a.class_mask = class_mask;
     hipError_t e = qmoe::launch_combine(a, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "moe_combine: launch");
     return MOE_OK;
@@ -663,7 +699,7 @@ int32_t moe_combine_complete(moe_ctx *ctx, void *y, uint8_t *complete, void *str
         ctx->unmarked.clear();
     }
     qmoe::CombineArgs a{};
-    a.out = at<float>(ctx, ctx->lay.out);
+    fill_out_source(ctx, a);
     a.topk_w = at<float>(ctx, ctx->lay.topk_w);
     a.inv = at<int32_t>(ctx, ctx->lay.inv);
     a.cls = at<uint8_t>(ctx, ctx->lay.cls);
@@ -692,7 +728,24 @@ int32_t moe_get(moe_ctx *ctx, int32_t what, const void **dev_ptr, size_t *bytes)
         case MOE_GET_OFFSETS: off = ctx->lay.off; sz = (2 * E + 1) * 4; break;
         case MOE_GET_PERM: off = ctx->lay.perm; sz = A * 4; break;
         case MOE_GET_INV: off = ctx->lay.inv; sz = A * 4; break;
-        case MOE_GET_EXPERT_OUT: off = ctx->lay.out; sz = A * (size_t)ctx->cfg.H * 4; break;
+        case MOE_GET_EXPERT_OUT:
+            off = ctx->lay.out; sz = A * (size_t)ctx->cfg.H * 4;
+            if (ctx->pending) return fail(MOE_E_STATE, "moe_get: an enqueued launch sequence is pending; call moe_expert_collect first");
+            if (!ctx->unreduced.empty()) {
+                // K-split context: the down projection left partial planes, which moe_combine adds on
+                // the fly; materialise the rows executed since the last request, behind the launches
+                // that produced them
+                std::vector<qmoe::Seg> segs;
+                segs.reserve(ctx->unreduced.size());
+                for (uint32_t u : ctx->unreduced)
+                    segs.push_back(qmoe::Seg{(uint32_t)ctx->units[u].row0, (uint16_t)ctx->units[u].rows, (uint16_t)ctx->units[u].expert});
+                hipError_t e = qmoe::launch_reduce_planes(segs.data(), (int)segs.size(), at<float>(ctx, ctx->lay.partial),
+                                                          at<float>(ctx, ctx->lay.out), ctx->cfg.H, ctx->lay.ksplit,
+                                                          (long)ctx->cfg.max_tokens * ctx->cfg.k * ctx->cfg.H, ctx->last_stream);
+                if (e != hipSuccess) return hip_fail(e, "moe_get: adding the partial planes");
+                ctx->unreduced.clear();
+            }
+            break;
         case MOE_GET_ACT: off = ctx->lay.act; sz = A * (size_t)ctx->cfg.F * es; break;
         case MOE_GET_UNITS: off = ctx->lay.units; sz = (size_t)ctx->n_units * sizeof(moe_unit); break;
         default: return fail(MOE_E_ARG, "moe_get: unknown item %d", what);

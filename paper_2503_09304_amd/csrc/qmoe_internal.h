@@ -40,6 +40,9 @@ struct RouteArgs {
 };
 hipError_t launch_route(const RouteArgs &a, hipStream_t s);
 
+// Records the text moe_last_error() returns on this thread and hands `code` back (printf-style).
+int32_t set_error(int32_t code, const char *fmt, ...);
+
 struct PermuteArgs {
     const int32_t *topk_idx;
     const uint8_t *prio;
@@ -89,10 +92,16 @@ struct ExpertArgs {
     int ksplit;                 // 1, 2 or 4 K ranges (down projection; fixed per context)
     int wave_cols;              // bf16 gate-up: columns per wave, 0 = chosen per launch
     float *partial;             // [ksplit][A][H] fp32 partial planes of the K-split down projection, or nullptr
+                                // (they stay as they are: moe_combine adds them, launch_reduce_planes on request)
     long plane;                 // elements per plane
     const int32_t *go;          // gate word of this launch on the device, or nullptr (see launch_gate)
 };
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
+
+// out[r,:] = ((p0 + p1) + p2) + p3 (p0 + p1 with two planes) for the rows of the segments: what
+// moe_combine computes on the fly, materialised for a caller that asks for the expert outputs.
+hipError_t launch_reduce_planes(const Seg *segs, int nseg, const float *partial, float *out, int H, int ksplit, long plane,
+                                hipStream_t s);
 
 // Re-layout of one [E][R][K] bf16 tensor into the packed block order (see MOE_W_PACKED).
 hipError_t launch_pack(const void *src, void *dst, int E, int R, int K, hipStream_t s);
@@ -102,7 +111,9 @@ hipError_t launch_pack_mxfp4(const void *codes, const void *scales, void *dcodes
 hipError_t launch_pack_gate(const void *Wg, void *WgT, int H, int E, hipStream_t s);
 
 struct CombineArgs {
-    const float *out;      // [A,H]
+    const float *out;      // [A,H]; with ksplit > 1: the first of ksplit partial planes, `plane` elements apart
+    int ksplit;            // 1, 2 or 4
+    long plane;
     const float *topk_w;   // [N,k]
     const int32_t *inv;    // [A]
     const uint8_t *cls;    // [N]
