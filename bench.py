@@ -49,6 +49,194 @@ def down_bytes(cfg, counts, es, ws, ksplit):
     return int(touched * cfg.H * cfg.F * ws) + cfg.A * cfg.F * es + cfg.A * cfg.H * 4 + planes
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def layer_bytes(cfg, counts, es, ws, passes="once"):
+    """Algorithmic HBM bytes of one pass of the whole layer: the three weight matrices of every expert
+    that has rows (once; or, passes="per_class", once per priority class in which it has rows: the
+    strict LS-phase-then-BE-phase order), x read by the router and gathered by the experts, the
+    activation written and read, the fp32 expert outputs written and read, y written."""
+    if passes == "per_class":
+        touched = int((counts[:, 0] > 0).sum()) + int((counts[:, 1] > 0).sum())
+    else:
+        touched = int((counts.sum(1) > 0).sum())
+    return (int(touched * 3 * cfg.F * cfg.H * ws) + cfg.N * cfg.H * es + cfg.A * cfg.H * es + 2 * cfg.A * cfg.F * es +
+            2 * cfg.A * cfg.H * 4 + cfg.N * cfg.H * es)
+
+
+def expert_boundaries(units):
+    return [i for i in range(1, len(units)) if units[i][0] != units[i - 1][0] or units[i][1] != units[i - 1][1]]
+
+
+def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
+    """Times one workload: K steps between two synchronisations with nothing else on the stream (the
+    figure of record), then the same loop again with HIP events around the gate-up launches, again
+    around the down launches, per stage, and per step."""
+    import numpy as np
+    import torch
+
+    import workloads as wl
+    from paper_2503_09304_amd.layer import GpuLayer
+
+    es = wl.elem_bytes(cfg)
+    ws = 0.5 + 1.0 / 32 if mx else es      # bytes per expert-weight element (4-bit code + its share of a scale byte)
+    # 4-bit weights on a decode-sized batch: a workgroup's K-iteration is bound by its conversions, two
+    # workgroups share a CU, and four K ranges (512 workgroups, one round) beat the two the
+    # configuration default would take (0.057-0.066 against 0.073 ms for the down projection).
+    force_ks = 4 if (mx and cfg.A <= 32 * cfg.E and cfg.F % 256 == 0) else 0
+    g = GpuLayer(inp, dw, down_ksplit=force_ks)
+    torch.cuda.synchronize()
+
+    def step():
+        g.route_permute()
+        g.run()
+        g.combine()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    counts = g.ctx.get("counts").cpu().numpy()
+    # ---- timed region: K steps, no event on the stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / steps
+    tokens_per_s = cfg.N / (ms_per_step * 1e-3)
+    # ---- the same loop with the gate-up launches bracketed by events on the launch stream, then the down launches
+    prof = {}
+    for kinds in (["gate_up"], ["down"]):
+        g.ctx.profile(kinds)
+        g.ctx.profile_read()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        prof.update({k: v for k, v in g.ctx.profile_read().items() if k in kinds})
+    g.ctx.profile(False)
+
+    # ---- per-stage times
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    acc = [0.0] * 4
+    for _ in range(5):
+        ev[0].record(); g.ctx.route(g.x, g.dw.struct, g.bias, n_tokens=cfg.N)
+        ev[1].record(); g.ctx.permute(g.prio)
+        ev[2].record(); g.run()
+        ev[3].record(); g.combine()
+        ev[4].record(); torch.cuda.synchronize()
+        for i in range(4):
+            acc[i] += ev[i].elapsed_time(ev[i + 1]) / 5
+    stages = dict(zip(("route_ms", "permute_ms", "experts_ms", "combine_ms"), (round(v, 4) for v in acc)))
+    # ---- spread of single steps
+    n_each = max(1, min(steps, 100))
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
+    for a, b in pairs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    each = np.array([a.elapsed_time(b) for a, b in pairs])
+    step_ms = {"median": round(float(np.median(each)), 4), "min": round(float(each.min()), 4),
+               "max": round(float(each.max()), 4), "n": n_each}
+
+    # ---- the same layer stopped and resumed at `cuts` seeded expert boundaries (throughput with the cuts)
+    with_cuts = None
+    if cuts:
+        units = g.ctx.units()
+        cps = wl.cut_points(cfg.seed, expert_boundaries(units), cuts)
+
+        def step_cut():
+            g.route_permute()
+            prev = 0
+            for c in cps:
+                g.run(c - prev)
+                prev = c
+            g.run()
+            g.combine()
+        for _ in range(3):
+            step_cut()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step_cut()
+        torch.cuda.synchronize()
+        ms_cut = (time.perf_counter() - t0) * 1e3 / steps
+        with_cuts = {"cuts_at_units": cps, "ms_per_step": round(ms_cut, 4), "tokens_per_s": round(cfg.N / (ms_cut * 1e-3), 1),
+                     "slowdown": round(ms_cut / ms_per_step, 4)}
+
+    # what down_ksplit = 0 picks (include/qmoe.h): the fewest K ranges that give every CU a workgroup
+    ksplit = 1
+    if cfg.N * cfg.k <= 256 * cfg.E:
+        wgs = cfg.E * ((cfg.H + 255) // 256)
+        if wgs >= 256:
+            ksplit = 1
+        elif 2 * wgs >= 256 and cfg.F % 128 == 0:
+            ksplit = 2
+        else:
+            ksplit = 4 if cfg.F % 256 == 0 else (2 if cfg.F % 128 == 0 else 1)
+    ksplit = force_ks or ksplit
+    gu_ms, gu_n = prof["gate_up"]
+    dn_ms, dn_n = prof["down"]
+    gu_avg_ms = gu_ms / max(gu_n, 1)
+    dn_avg_ms = dn_ms / max(dn_n, 1)
+    gub = gate_up_bytes(cfg, counts, es, ws)
+    dnb = down_bytes(cfg, counts, es, ws, ksplit)
+    flops = wl.flops(cfg)
+    gu_flops = 4.0 * cfg.A * cfg.H * cfg.F
+    hbm_bound = (gub / (HBM_PEAK_GBS * 1e9)) >= (gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+    if hbm_bound:
+        achieved = gub / (gu_avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4)}
+    else:
+        achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4)}
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name + ("_mxfp4" if mx else "")) if not rowmajor else None
+    roof.update({"kernel": "expert_bf16 gate-up (W1,W3 GEMM + SwiGLU)", "avg_launch_ms": round(gu_avg_ms, 4),
+                 "launches": gu_n, "timed_by": "HIP events on the launch stream around every gate-up launch, in a loop "
+                                               "of the same K steps run right after the timed region",
+                 "algorithmic_bytes_per_launch": int(gub),
+                 "algorithmic_flops_per_launch": gu_flops,
+                 "down_avg_launch_ms": round(dn_avg_ms, 4),
+                 "down_algorithmic_bytes_per_launch": int(dnb),
+                 "down_achieved_GBps": round(dnb / (dn_avg_ms * 1e-3) / 1e9, 1) if dn_ms > 0 else None,
+                 "down_achieved_TFLOPs": round(2.0 * cfg.A * cfg.H * cfg.F / (dn_avg_ms * 1e-3) / 1e12, 1) if dn_ms > 0 else None})
+    lb = layer_bytes(cfg, counts, es, ws)
+    if hbm_bound:
+        la = lb / (ms_per_step * 1e-3) / 1e9
+        layer = {"bound": "hbm", "algorithmic_bytes": int(lb), "achieved": round(la, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": round(la / HBM_PEAK_GBS, 4)}
+    else:
+        la = flops / (ms_per_step * 1e-3) / 1e12
+        layer = {"bound": "mfma", "algorithmic_flops": flops, "achieved": round(la, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                 "unit": "TFLOP/s", "frac": round(la / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return {"workload": cfg.name, "ms_per_step": ms_per_step, "tokens_per_s": round(tokens_per_s, 1),
+            "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "layer": layer, "stages_ms": stages,
+            "step_ms": step_ms, "roofline": roof, "with_cuts": with_cuts, "_layer": g, "_ws": ws}
+
+
+def compact(r):
+    """The sub-record of a workload other than the headline one."""
+    ro = r["roofline"]
+    out = {"ms_per_step": round(r["ms_per_step"], 4), "tokens_per_s": r["tokens_per_s"], "layer_tflops": r["layer_tflops"],
+           "layer": r["layer"],
+           "gate_up": {k: ro[k] for k in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_ms", "traffic",
+                                          "algorithmic_bytes_per_launch")},
+           "down": {"avg_launch_ms": ro["down_avg_launch_ms"], "GBps": ro["down_achieved_GBps"], "TFLOPs": ro["down_achieved_TFLOPs"]}}
+    if r["with_cuts"]:
+        out["with_4_preempt_resume_cuts"] = r["with_cuts"]
+    return out
+
+
 def pct(v, p):
     import numpy as np
     return float(np.percentile(np.asarray(v), p))
@@ -233,6 +421,7 @@ def serve_bench(args) -> int:
 
     import paper_2503_09304_amd as q
     import workloads as wl
+    import serve_glue
     from paper_2503_09304_amd import serve
 
     if not torch.cuda.is_available():
@@ -242,7 +431,8 @@ def serve_bench(args) -> int:
     ensure_built()
     q.lib()
     c = wl.CONFIGS["cfg2"]
-    w, keep = serve.synthetic_weights(c.E, c.H, c.F, seed=c.weight_seed or c.seed)
+    w, keep = serve_glue.synthetic_weights(c.E, c.H, c.F, seed=c.weight_seed or c.seed)
+    glue = serve_glue.SyntheticGlue(c.H, c.k)
     rates = [float(r) for r in args.serve_rates.split(",")]
     rows = []
     for rate in rates:
@@ -252,7 +442,7 @@ def serve_bench(args) -> int:
         for pre in (False, True):
             jobs = [serve.Job(i, float(d["arrival_s"][i]), q.SCHED_LS if d["is_ls"][i] else q.SCHED_BE,
                               int(d["prompt_len"][i]), int(d["out_len"][i])) for i in range(args.serve_jobs)]
-            eng = serve.Engine(w, c.E, c.k, c.H, c.F, layers=args.serve_layers, batch_size=32,
+            eng = serve.Engine(w, glue, c.E, c.k, c.H, c.F, layers=args.serve_layers, batch_size=32,
                                max_prompt=args.serve_max_prompt, preemptive=pre, units_per_call=args.units_per_call,
                                lookahead=args.lookahead, chunk_rows=c.chunk_rows)
             warm = [serve.Job(i, 0.0, q.SCHED_BE, args.serve_max_prompt, 2) for i in range(4)]
@@ -294,6 +484,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the sub-records of cfg4, cfg3_be and cfg5 that the default (cfg2) run adds")
     ap.add_argument("--rowmajor", action="store_true", help="keep the weights row-major (default: packed at load)")
     ap.add_argument("--weights", default="bf16", choices=["bf16", "mxfp4"],
                     help="expert weight format: bf16 (the headline workload) or 4-bit microscaling FP4")
@@ -326,11 +518,9 @@ def main() -> int:
     ensure_built()  # what is built is what runs; built here only if there is nothing
     q.lib()  # fail loudly if the HIP library is missing
     cfg = wl.CONFIGS[args.workload]
-    es = wl.elem_bytes(cfg)
     log("workload", wl.describe(cfg))
     t0 = time.time()
     mx = args.weights == "mxfp4"
-    ws = 0.5 + 1.0 / 32 if mx else es      # bytes per expert-weight element (4-bit code + its share of a scale byte)
     if mx:
         from paper_2503_09304_amd.layer import DevWeightsMX
         w4 = wl.make_weights_mxfp4(cfg)
@@ -344,11 +534,6 @@ def main() -> int:
         dw = DevWeights(inp.w)
         if not args.rowmajor:
             dw = dw.packed()      # one-time re-layout at model load, outside the timed region
-    # 4-bit weights on a decode-sized batch: a workgroup's K-iteration is bound by its conversions, two
-    # workgroups share a CU, and four K ranges (512 workgroups, one round) beat the two the
-    # configuration default would take (0.057-0.066 against 0.073 ms for the down projection).
-    force_ks = 4 if (mx and cfg.A <= 32 * cfg.E and cfg.F % 256 == 0) else 0
-    g = GpuLayer(inp, dw, down_ksplit=force_ks)
     torch.cuda.synchronize()
     if args.calib_copy:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
@@ -357,96 +542,16 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    def step():
-        g.route_permute()
-        g.run()
-        g.combine()
+    m = measure(cfg, inp, dw, args.steps, args.warmup, mx, args.rowmajor)
+    g = m.pop("_layer")
+    ms_per_step = m["ms_per_step"]
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    counts = g.ctx.get("counts").cpu().numpy()
-    # Timed region: only the dominant kernel (gate-up) is bracketed with events, since every bracketed
-    # launch costs a few microseconds of stream time; the down kernels are timed in a loop of their own.
-    g.ctx.profile(["gate_up"])
-    g.ctx.profile_read()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = g.ctx.profile_read()
-    ms_per_step = dt * 1e3 / args.steps
-    tokens_per_s = cfg.N / (ms_per_step * 1e-3)
-    g.ctx.profile(["down", "down_reduce"])
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof.update({k: v for k, v in g.ctx.profile_read().items() if k != "gate_up"})
-    g.ctx.profile(False)
-
-    # ---- per-stage times (separate loop, for the log only)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
-    acc = [0.0] * 4
-    for _ in range(5):
-        ev[0].record(); g.ctx.route(g.x, g.dw.struct, g.bias, n_tokens=cfg.N)
-        ev[1].record(); g.ctx.permute(g.prio)
-        ev[2].record(); g.run()
-        ev[3].record(); g.combine()
-        ev[4].record(); torch.cuda.synchronize()
-        for i in range(4):
-            acc[i] += ev[i].elapsed_time(ev[i + 1]) / 5
-    stages = dict(zip(("route_ms", "permute_ms", "experts_ms", "combine_ms"), (round(v, 4) for v in acc)))
-    # ---- spread of single steps (events around each step; the timed region above is the figure of record)
-    n_each = max(1, min(args.steps, 100))
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
-    for a, b in pairs:
-        a.record(); step(); b.record()
-    torch.cuda.synchronize()
-    each = np.array([a.elapsed_time(b) for a, b in pairs])
-    step_ms = {"median": round(float(np.median(each)), 4), "min": round(float(each.min()), 4),
-               "max": round(float(each.max()), 4), "n": n_each}
-
-    # what down_ksplit = 0 picks (include/qmoe.h): the fewest K ranges that give every CU a workgroup
-    ksplit = 1
-    if cfg.N * cfg.k <= 256 * cfg.E:
-        wgs = cfg.E * ((cfg.H + 255) // 256)
-        if wgs >= 256:
-            ksplit = 1
-        elif 2 * wgs >= 256 and cfg.F % 128 == 0:
-            ksplit = 2
-        else:
-            ksplit = 4 if cfg.F % 256 == 0 else (2 if cfg.F % 128 == 0 else 1)
-    ksplit = force_ks or ksplit
-    gu_ms, gu_n = prof["gate_up"]
-    dn_ms = prof["down"][0] + prof["down_reduce"][0]
-    gu_avg_ms = gu_ms / max(gu_n, 1)
-    gub = gate_up_bytes(cfg, counts, es, ws)
-    dnb = down_bytes(cfg, counts, es, ws, ksplit)
-    flops = wl.flops(cfg)
-    gu_flops = 4.0 * cfg.A * cfg.H * cfg.F
-    hbm_bound = (gub / (HBM_PEAK_GBS * 1e9)) >= (gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12))
-    if hbm_bound:
-        achieved = gub / (gu_avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4)}
-    else:
-        achieved = gu_flops / (gu_avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4)}
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name + ("_mxfp4" if mx else "")) if not args.rowmajor else None
-    roof.update({"kernel": "expert_bf16 gate-up (W1,W3 GEMM + SwiGLU)", "avg_launch_ms": round(gu_avg_ms, 4),
-                 "launches": gu_n, "algorithmic_bytes_per_launch": int(gub),
-                 "algorithmic_flops_per_launch": gu_flops,
-                 "down_kernels_ms_per_step": round(dn_ms / max(args.steps, 1), 4),
-                 "down_algorithmic_bytes_per_step": int(dnb),
-                 "down_achieved_GBps": round(dnb / (dn_ms / max(args.steps, 1) * 1e-3) / 1e9, 1) if dn_ms > 0 else None})
-
-    # ---- LS tokens first inside a mixed batch: run the LS units, combine the LS rows, then the rest
+    # ---- LS tokens first inside a mixed batch (the strict priority-major order: every LS unit, the LS
+    # rows combined, then every BE unit): two passes over the weights of experts that hold both classes
     ls_first = None
     n_ls_units = sum(1 for u in g.ctx.units() if u[1] == 0)
     if 0 < n_ls_units < g.ctx.cursor.n_units:
+        counts = g.ctx.get("counts").cpu().numpy()
         t_ls, t_all = [], []
         for _ in range(10):
             torch.cuda.synchronize()
@@ -461,13 +566,20 @@ def main() -> int:
             t_ls.append(time.perf_counter() - t0)
             torch.cuda.synchronize()
             t_all.append(time.perf_counter() - t0)
-        ls_first = {"ls_rows_ready_ms": round(1e3 * float(np.median(t_ls)), 4), "whole_batch_ms": round(1e3 * float(np.median(t_all)), 4),
+        two_pass_bytes = layer_bytes(cfg, counts, wl.elem_bytes(cfg), m["_ws"], passes="per_class")
+        whole = float(np.median(t_all))
+        ls_first = {"ls_rows_ready_ms": round(1e3 * float(np.median(t_ls)), 4), "whole_batch_ms": round(1e3 * whole, 4),
+                    "tokens_per_s": round(cfg.N / whole, 1),
+                    "algorithmic_bytes": int(two_pass_bytes),
+                    "layer_GBps": round(two_pass_bytes / whole / 1e9, 1),
+                    "layer_frac_of_hbm_peak": round(two_pass_bytes / whole / 1e9 / HBM_PEAK_GBS, 4),
                     "single_call_ms": round(ms_per_step, 4), "ls_units": n_ls_units, "units": int(g.ctx.cursor.n_units)}
         log("LS-first inside the mixed batch:", json.dumps(ls_first))
 
     # ---- LS latency while a long BE batch is in flight (Mixtral weights)
     lat = None
-    if args.latency_trials > 0 and cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx:
+    mixtral = cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx and not args.rowmajor
+    if args.latency_trials > 0 and mixtral:
         lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
                          be_ksplit=args.be_ksplit)
         own = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
@@ -475,6 +587,24 @@ def main() -> int:
         lat["ls_on_own_stream"] = {"ls_latency_ms": own["ls_latency_ms"], "device_stop": own["device_stop"],
                                    "be_output_bit_identical_after_resume": own["be_output_bit_identical_after_resume"]}
         log("LS latency under BE load:", json.dumps(lat))
+
+    # ---- the other workloads the targets are stated on, as compact sub-records of the same run
+    others = {}
+    if not args.no_other_workloads and args.workload == "cfg2" and mixtral:
+        for name in ("cfg4", "cfg3_be"):
+            c = wl.CONFIGS[name]
+            r = measure(c, wl.make_inputs(c, weights={}), dw, args.steps, max(3, args.warmup // 2), False, False)
+            r.pop("_layer")
+            others[name] = compact(r)
+            log(name, json.dumps(others[name]))
+        c = wl.CONFIGS["cfg5"]
+        i5 = wl.make_inputs(c)
+        dw5 = DevWeights(i5.w).packed()
+        r = measure(c, i5, dw5, args.steps, max(3, args.warmup // 2), False, False, cuts=4)
+        r.pop("_layer")
+        others["cfg5"] = compact(r)
+        log("cfg5", json.dumps(others["cfg5"]))
+        del dw5, i5
 
     # ---- the oracle, as it stands, on a bounded sample of the same workload
     cpu = None
@@ -488,13 +618,24 @@ def main() -> int:
         lay.run()
         y_ref, _ = lay.y()
         t_cpu = time.perf_counter() - t0
-        cpu = {"value": round(ns / t_cpu, 3), "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
-               "sample": f"first {ns} tokens of the {cfg.name} batch through the whole layer (fp64, {t_cpu:.1f} s)"}
-        log(f"oracle: {ns} tokens in {t_cpu:.1f}s on {oracle.threads()} threads")
+        nthreads = oracle.threads()
+        # one thread, the tiny fp32 layer (cfg1): the oracle's per-core speed
+        c1 = wl.CONFIGS["cfg1"]
+        i1 = wl.make_inputs(c1)
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        l1 = oracle.OracleLayer(i1.x, i1.w, i1.prio, i1.bias, c1.k, c1.chunk_rows)
+        l1.run(); l1.y()
+        t_one = time.perf_counter() - t0
+        oracle.set_threads(nthreads)
+        cpu = {"value": round(ns / t_cpu, 3), "unit": "tokens/s", "cores": nthreads, "kind": "oracle",
+               "sample": f"first {ns} tokens of the {cfg.name} batch through the whole layer (fp64, {t_cpu:.1f} s)",
+               "cpu_model": cpu_model(), "cfg1_single_thread_ms": round(1e3 * t_one, 3)}
+        log(f"oracle: {ns} tokens in {t_cpu:.1f}s on {nthreads} threads ({cpu_model()}); cfg1 on one thread {1e3 * t_one:.2f} ms")
 
     out = {
         "metric": "MoE-layer tokens/s + % MFMA/HBM roofline (Mixtral shape); LS latency under BE load",
-        "value": round(tokens_per_s, 1),
+        "value": m["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -512,11 +653,18 @@ def main() -> int:
                    "weights": ("4-bit microscaling FP4 (e2m1 + e8m0 per 32), packed at load" if mx else
                                "row-major" if args.rowmajor else "packed at load (moe_pack_weights)"),
                    "units": int(g.ctx.cursor.n_units)},
-        "layer_tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
-        "stages_ms": stages,
-        "step_ms": step_ms,
-        "roofline": roof,
-        "ls_first_in_mixed_batch": ls_first,
+        "layer_tflops": m["layer_tflops"],
+        "layer_roofline": m["layer"],
+        "stages_ms": m["stages_ms"],
+        "step_ms": m["step_ms"],
+        "roofline": m["roofline"],
+        "execution_order": {
+            "value_is": "merged_single_call",
+            "merged_single_call": {"ms": round(ms_per_step, 4), "tokens_per_s": m["tokens_per_s"],
+                                   "what": "one call spans both phases; an expert's LS and BE rows share one pass over its weights"},
+            "priority_major_two_phase": ls_first,
+        },
+        "other_workloads": others or None,
         "ls_latency_under_be_load": lat,
         "cpu_baseline": cpu,
     }

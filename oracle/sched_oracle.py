@@ -1,8 +1,7 @@
 """Oracle of the host scheduler: dispatcher, four FCFS queues, batch selection (test infrastructure).
 
-Plain Python lists, written step by step in the order of the paper's "Batch Selection Logic"
-algorithm (section "System Architecture", Algorithm 1) and of its description of the dispatcher
-(same section): new jobs enter the prefill queue of their priority class, every model output token
+Plain Python lists.  The batch selection of the paper's section "System Architecture" (Algorithm 1)
+is stated as a rule over the four queues, the dispatcher as that section describes it: new jobs enter the prefill queue of their priority class, every model output token
 sends its job to the decode queue of its class, the batch engine builds the next batch from the four
 queues.  Only tests, the smoke check and the benchmark's baseline leg may import this module; the
 product scheduler is the C++ one behind include/qsched.h and shares no code with it.
@@ -55,27 +54,26 @@ class SchedOracle:
         return taken
 
     def next_batch(self):
-        """Algorithm 1.  Returns (jobs, stage, number of LS jobs) or None."""
+        """Batch selection (Algorithm 1) stated as a rule.  Which (class, stage) leads the batch:
+        latency-sensitive decode work if a whole batch of it waits; otherwise the first non-empty
+        queue in the order LS prefill, LS decode, BE decode, BE prefill.  A batch led by LS jobs that
+        is not full is topped up with best-effort jobs of the same stage; a batch led by BE jobs
+        holds BE jobs only.  Returns (jobs, stage, number of LS jobs) or None when nothing waits."""
         B = self.batch_size
-        if len(self.ls_decode) >= B:
-            batch, stage = self._get_batch(self.ls_decode, B), DECODE
-            n_ls = len(batch)
-        elif self.ls_prefill:
-            batch, stage = self._get_batch(self.ls_prefill, B), PREFILL
-            n_ls = len(batch)
-            if len(batch) < B:
-                batch += self._get_batch(self.be_prefill, B - len(batch))
-        elif self.ls_decode:
-            batch, stage = self._get_batch(self.ls_decode, B), DECODE
-            n_ls = len(batch)
-            if len(batch) < B:
-                batch += self._get_batch(self.be_decode, B - len(batch))
-        elif self.be_decode:
-            batch, stage, n_ls = self._get_batch(self.be_decode, B), DECODE, 0
-        elif self.be_prefill:
-            batch, stage, n_ls = self._get_batch(self.be_prefill, B), PREFILL, 0
+        queue = {(LS, PREFILL): self.ls_prefill, (LS, DECODE): self.ls_decode,
+                 (BE, PREFILL): self.be_prefill, (BE, DECODE): self.be_decode}
+        if len(queue[LS, DECODE]) >= B:
+            lead = (LS, DECODE)
         else:
-            return None
+            waiting = [key for key in ((LS, PREFILL), (LS, DECODE), (BE, DECODE), (BE, PREFILL)) if queue[key]]
+            if not waiting:
+                return None
+            lead = waiting[0]
+        cls, stage = lead
+        batch = self._get_batch(queue[lead], B)
+        n_ls = len(batch) if cls == LS else 0
+        if cls == LS:
+            batch += self._get_batch(queue[BE, stage], B - len(batch))
         self.running.update(batch)
         return batch, stage, n_ls
 

@@ -6,11 +6,21 @@ Paper: section "System Architecture" (scheduler, dispatcher, batch engine, close
 and scheduler) and the evaluation's workload and metrics (Poisson arrivals, a fraction of the
 prompts marked LS, time to first token, turnaround time, job completion rate).
 
-What is modelled.  A model is `layers` MoE layers; the hidden state entering layer l+1 is x + y of
-layer l (a residual stand-in for the attention block, done with a torch add: the blocks between MoE
-layers are not part of this library).  A prefill iteration runs all prompt tokens of the batch's
-jobs through the stack and yields each job's first token; a decode iteration runs one token per
-job.  Hidden states are rows of a fixed seeded bank, selected by (job, token index).
+What is modelled.  A model is `layers` MoE layers.  Everything between two MoE layers (in a real
+model the attention block and the residual) and the source of the hidden states are not part of this
+library: the caller passes a `glue` object that supplies them (serve_glue.py at the repository root
+is the synthetic one the benchmark and the tests use: rows of a seeded bank as hidden states, x + y
+as the stand-in for the block between layers).  This module only drives the scheduler and the layer
+calls; PyTorch appears in it for device buffers, events and host-to-device copies of index arrays.
+A prefill iteration runs all prompt tokens of the batch's jobs through the stack and yields each
+job's first token; a decode iteration runs one token per job.
+
+The glue object:
+    glue.fill_inputs(x, rows, n)        x[:n] <- the hidden states of bank rows rows[:n] (device tensors)
+    glue.between_layers(x, y)           x <- input of the next layer, from this layer's input x and output y
+    glue.bank_rows                      number of rows the bank holds
+    glue.observe_layer(ctx, n_ls_rows)  optional hook after moe_permute of every layer (tests)
+    glue.observe_output(x, owner, n)    optional hook after the last layer (tests: per-job digests)
 
 Two policies share all of that code:
   * preemptive=True: jobs keep their class; while a batch of BE jobs only is executing, the loop keeps
@@ -51,25 +61,6 @@ class Job:
     done_s: float = -1.0
 
 
-def synthetic_weights(E: int, H: int, F: int, seed: int, device="cuda:0"):
-    """Seeded N(0, 0.02^2) bf16 weights generated on the device, re-laid-out for the expert kernels."""
-    g = torch.Generator(device=device)
-    g.manual_seed(seed)
-
-    def rnd(*shape):
-        return (torch.randn(*shape, generator=g, device=device, dtype=torch.float32) * 0.02).to(torch.bfloat16)
-
-    Wg = rnd(H, E)
-    W1, W3, W2 = rnd(E, F, H), rnd(E, F, H), rnd(E, H, F)
-    src = q.Context.weights(Wg, W1, W3, W2)
-    pWg = torch.empty(((E + 15) // 16 * 16, H), dtype=torch.bfloat16, device=device)
-    pW1, pW3, pW2 = torch.empty_like(W1), torch.empty_like(W3), torch.empty_like(W2)
-    dst = q.Context.weights(pWg, pW1, pW3, pW2)
-    q.moe_pack_weights(q.MoeConfig(E, 1, H, F, q.MOE_BF16, 1, 0), src, dst)
-    torch.cuda.synchronize()
-    return dst, (pWg, pW1, pW3, pW2)     # the struct and the tensors that keep its memory alive
-
-
 class _Slot:
     """Buffers and context of one in-flight batch of one stage."""
 
@@ -86,24 +77,21 @@ class _Slot:
 
 
 class Engine:
-    def __init__(self, weights: q.MoeWeights, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
+    def __init__(self, weights: q.MoeWeights, glue, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
                  max_prompt: int, preemptive: bool, units_per_call: int = 4, lookahead: int = 1, chunk_rows: int = 256,
-                 bank_rows: int = 4096, seed: int = 1, digest: bool = False, device_stop: bool = True, device="cuda:0"):
+                 device_stop: bool = True, device="cuda:0"):
         self.w, self.layers, self.batch_size, self.max_prompt = weights, layers, batch_size, max_prompt
         self.preemptive, self.units_per_call, self.lookahead = preemptive, units_per_call, lookahead
         self.device_stop = device_stop
         self.device = device
-        g = torch.Generator(device=device)
-        g.manual_seed(seed)
-        self.bank = torch.randn(bank_rows, H, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
-        self.bank_rows = bank_rows
+        self.glue = glue
+        self.bank_rows = glue.bank_rows
         # [stage][level]: level 1 holds the batch that runs while a level-0 batch is parked
         self.slots = {
             q.SCHED_PREFILL: [_Slot(E, k, H, F, chunk_rows, batch_size * max_prompt, device) for _ in range(2)],
             q.SCHED_DECODE: [_Slot(E, k, H, F, chunk_rows, batch_size, device) for _ in range(2)],
         }
         self.sched = q.Scheduler(batch_size)
-        self.digest_on = digest
         self.trace: list = []        # scheduler calls in order, for replay against the oracle
 
     # ---- dispatcher side ----
@@ -142,20 +130,21 @@ class Engine:
         slot.rows[:n].copy_(torch.from_numpy(rows.astype(np.int64)))
         slot.prio[:n].copy_(torch.from_numpy(prio))
         slot.owner[:n].copy_(torch.from_numpy(owner))
-        torch.index_select(self.bank, 0, slot.rows[:n], out=slot.x[:n])
-        return n
+        self.glue.fill_inputs(slot.x, slot.rows, n)
+        return n, int(prio.sum())
 
     def _iteration(self, jobs, stage, n_ls, level: int) -> None:
         slot = self.slots[stage][level]
-        n = self._build(slot, jobs, stage, n_ls)
+        n, n_ls_rows = self._build(slot, jobs, stage, n_ls)
         x, y, ctx = slot.x[:n], slot.y[:n], slot.ctx
+        observe_layer = getattr(self.glue, "observe_layer", None)
+        observe_output = getattr(self.glue, "observe_output", None)
         preemptible = self.preemptive and level == 0 and n_ls == 0
         for _ in range(self.layers):
             ctx.route(x, self.w, n_tokens=n)
             ctx.permute(slot.prio)
-            if self.digest_on:      # rows the layer queued as LS, against what the batch holds
-                self.ls_rows_seen += ctx.get("counts")[:, 0].sum()
-                self.ls_rows_expected += ctx.cfg.k * int(slot.prio[:n].sum().item())
+            if observe_layer is not None:
+                observe_layer(ctx, n_ls_rows)
             if not preemptible:
                 ctx.expert_run(x, self.w)
             elif self.device_stop and stage == q.SCHED_PREFILL:
@@ -198,10 +187,9 @@ class Engine:
                         pending.append(ev)
                         done = rc == q.MOE_DONE
             ctx.combine(y)
-            x.add_(y)
-        if self.digest_on:
-            h = x.view(torch.int16).to(torch.int32).sum(1, dtype=torch.int64)
-            self.digest.index_add_(0, slot.owner[:n], h)
+            self.glue.between_layers(x, y)
+        if observe_output is not None:
+            observe_output(x, slot.owner, n)
         torch.cuda.current_stream().synchronize()
         now = self._now()
         self.iterations[stage] += 1
@@ -223,9 +211,6 @@ class Engine:
         self.arrivals = sorted(jobs, key=lambda j: (j.arrival_s, j.id))
         self.next_arrival, self.finished, self.preemptions = 0, 0, 0
         self.iterations = {q.SCHED_PREFILL: 0, q.SCHED_DECODE: 0}
-        self.digest = torch.zeros(max(self.jobs) + 1, dtype=torch.int64, device=self.device)
-        self.ls_rows_seen = torch.zeros((), dtype=torch.int64, device=self.device)
-        self.ls_rows_expected = 0
         assert all(1 <= j.prompt_len <= self.max_prompt and j.out_len >= 1 for j in jobs)
         torch.cuda.synchronize()
         self.t0 = time.perf_counter()
