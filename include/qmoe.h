@@ -181,6 +181,20 @@ int32_t moe_pack_weights(const moe_config *cfg, const moe_weights *src, moe_weig
 int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weights *w,
                   const float *logit_bias, void *stream);
 
+/* The router for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels and same results as moe_route with row-major
+ * weights, bit for bit, but no context, no workspace and no allocation of any kind (device, pinned or
+ * host): the one scratch buffer the bf16 router needs (Wg transposed and padded, ceil16(E)*H bf16)
+ * lives in a 2 MiB array in the library's device image, one copy per GPU, held until the process ends.
+ *   cfg: E, k, H and dtype are used.  x [device] [n_tokens,H]; Wg [device] [H,E] row-major;
+ *   logit_bias [device] float[E] or NULL; outputs [device]: logits float[n_tokens,E], topk_idx
+ *   int32[n_tokens,k], topk_w float[n_tokens,k].
+ * MOE_E_ARG if ceil16(E)*H*2 exceeds 2 MiB (bf16) or an argument is bad; nothing is enqueued then.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different streams,
+ * different threads) race; calls on one stream are ordered and each rewrites what it reads. */
+int32_t moe_route_noalloc(const moe_config *cfg, const void *x, int32_t n_tokens, const void *Wg,
+                          const float *logit_bias, float *logits, int32_t *topk_idx, float *topk_w, void *stream);
+
 /* Per-expert priority queues (Sec. 3.3 per-expert FIFO; Sec. 3.2 LS before BE): a stable counting
  * sort of the n_tokens*k assignments by (expert ascending, LS before BE, token ascending).
  * prio [device] uint8[n_tokens], non-zero = LS.  Produces counts, offsets, perm, inv and the

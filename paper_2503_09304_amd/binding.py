@@ -61,6 +61,13 @@ SCHED_Q_LS_PREFILL, SCHED_Q_BE_PREFILL, SCHED_Q_LS_DECODE, SCHED_Q_BE_DECODE = 0
 _lib = None
 
 
+def moe_route_noalloc(cfg: "MoeConfig", x, n_tokens: int, Wg, bias, logits, topk_idx, topk_w) -> int:
+    """The router without context, workspace or allocation (see include/qmoe.h); tensors or raw addresses."""
+    rc = lib().moe_route_noalloc(C.byref(cfg), _ptr(x), n_tokens, _ptr(Wg), _ptr(bias), _ptr(logits), _ptr(topk_idx),
+                                 _ptr(topk_w), _stream())
+    return _check(rc)
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -77,6 +84,8 @@ def lib():
         L.moe_workspace_bytes.argtypes = [C.POINTER(MoeConfig)]
         L.moe_create.argtypes = [C.POINTER(MoeConfig), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
         L.moe_destroy.argtypes = [C.c_void_p]
+        L.moe_route_noalloc.argtypes = [C.POINTER(MoeConfig), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p]
         L.moe_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(MoeWeights), C.c_void_p, C.c_void_p]
         L.moe_permute.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeCursor), C.c_void_p]
         L.moe_expert_run.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(MoeWeights), C.c_uint32,

@@ -13,7 +13,15 @@
 // LDS (order: logit desc, index asc).  fp32: k rounds of a wave-wide arg-max over the same order.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "qmoe_internal.h"
+
+// Scratch of moe_route_noalloc: the router weight transposed and padded, bf16 [ceil16(E)][H].  One
+// copy per GPU the library runs on, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels get the device address that call returns.
+constexpr size_t kRouteScratchBytes = 2u << 20;
+static __device__ __align__(256) unsigned char scratch[kRouteScratchBytes];
 
 namespace qmoe {
 namespace {
@@ -312,3 +320,50 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s) {
 }
 
 }  // namespace qmoe
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once looked up
+}  // namespace
+
+extern "C" int32_t moe_route_noalloc(const moe_config *cfg, const void *x, int32_t n_tokens, const void *Wg,
+                                     const float *logit_bias, float *logits, int32_t *topk_idx, float *topk_w, void *stream) {
+    using qmoe::set_error;
+    if (!cfg) return set_error(MOE_E_ARG, "moe_route_noalloc: null config");
+    if (cfg->E < 1 || cfg->E > qmoe::kMaxExperts || cfg->k < 1 || cfg->k > cfg->E || cfg->k > qmoe::kMaxTopK || cfg->H < 1 ||
+        (cfg->dtype != MOE_F32 && cfg->dtype != MOE_BF16) || (cfg->dtype == MOE_BF16 && cfg->H % 64))
+        return set_error(MOE_E_ARG, "moe_route_noalloc: bad configuration (E 1..256, k 1..min(E,32), bf16 needs H a multiple of 64)");
+    if (n_tokens < 0 || (int64_t)n_tokens * cfg->k >= (int64_t)1 << 31) return set_error(MOE_E_ARG, "moe_route_noalloc: n_tokens out of range");
+    if (!Wg || !logits || !topk_idx || !topk_w || (n_tokens > 0 && !x)) return set_error(MOE_E_ARG, "moe_route_noalloc: null pointer");
+    const size_t need = cfg->dtype == MOE_BF16 ? (size_t)((cfg->E + 15) / 16 * 16) * (size_t)cfg->H * 2 : 0;
+    if (need > kRouteScratchBytes)
+        return set_error(MOE_E_ARG, "moe_route_noalloc: ceil16(E)*H*2 = %zu bytes exceed the %zu-byte static scratch", need,
+                         (size_t)kRouteScratchBytes);
+    if (n_tokens == 0) return MOE_OK;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_error(MOE_E_HIP, "moe_route_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return set_error(MOE_E_ARG, "moe_route_noalloc: device %d out of range", dev);
+    void *ptr;
+    {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p)
+                return set_error(MOE_E_HIP, "moe_route_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    qmoe::RouteArgs a{};
+    a.x = x; a.Wg = Wg; a.bias = logit_bias;
+    a.WgT = ptr;                  // every element the kernels read is rewritten by this call's transpose first
+    a.logits = logits; a.topk_idx = topk_idx; a.topk_w = topk_w;
+    a.N = n_tokens; a.H = cfg->H; a.E = cfg->E; a.k = cfg->k; a.dtype = cfg->dtype;
+    a.packed = false;
+    e = qmoe::launch_route(a, (hipStream_t)stream);
+    if (e != hipSuccess) return set_error(MOE_E_HIP, "moe_route_noalloc: launch: %s", hipGetErrorString(e));
+    return MOE_OK;
+}
