@@ -242,13 +242,15 @@ def pct(v, p):
     return float(np.percentile(np.asarray(v), p))
 
 
-def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be_ksplit=0, seed=77, ls_own_stream=False):
+def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be_ksplit=0, seed=77, ls_own_stream=False,
+               units_per_launch=None):
     """LS completion latency when a BE prompt is in flight (cfg3): the BE context is fed
     `units_per_call` work units per moe_expert_run with at most `lookahead` calls outstanding; at a
     seeded offset into the BE layer an LS batch arrives, the host stops feeding BE, runs the LS
     context to completion and resumes BE from its cursor.  Latency = arrival -> the host sees the
     LS combine finished."""
     import numpy as np
+    upl = units_per_launch or q.UINT32_MAX         # launch size of the enqueued (device-stopped) sequence: default the whole layer
     cbe, cls_ = wl.CONFIGS["cfg3_be"], wl.CONFIGS["cfg3_ls"]
     be = GpuLayer(wl.make_inputs(cbe, weights={}), dw, down_ksplit=be_ksplit)
     ls = GpuLayer(wl.make_inputs(cls_, weights={}), dw)
@@ -316,7 +318,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
     # the BE layer enqueued whole as gated launches (moe_expert_enqueue), nothing arriving
     def enqueue_be():
         be.route_permute()
-        while be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call) != q.MOE_DONE:
+        while be.ctx.expert_enqueue(be.x, be.dw.struct, upl) != q.MOE_DONE:
             if be.ctx.expert_collect() == q.MOE_DONE:
                 break
         be.combine()
@@ -379,7 +381,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         be.route_permute()
-        rc = be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call)
+        rc = be.ctx.expert_enqueue(be.x, be.dw.struct, upl)
         while time.perf_counter() - t0 < off:
             pass
         be.ctx.expert_stop()
@@ -388,7 +390,7 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         while rc != q.MOE_DONE:
             rc = be.ctx.expert_collect()
             if rc != q.MOE_DONE:
-                rc = be.ctx.expert_enqueue(be.x, be.dw.struct, units_per_call)
+                rc = be.ctx.expert_enqueue(be.x, be.dw.struct, upl)
         be.combine()
         torch.cuda.synchronize()
         if i < 8:
@@ -405,7 +407,8 @@ def ls_latency(wl, q, torch, GpuLayer, dw, trials, units_per_call, lookahead, be
         "be_layer_fed_with_lookahead_ms": round(be_fed_ms, 4),
         "be_down_ksplit": be_ksplit,
         "device_stop": {"ls_latency_ms": {"p50": ms(pct(lat_dev, 50)), "p99": ms(pct(lat_dev, 99)), "max": ms(max(lat_dev))},
-                        "be_layer_enqueued_ms": round(be_enq_ms, 4), "units_per_launch": units_per_call,
+                        "be_layer_enqueued_ms": round(be_enq_ms, 4),
+                        "units_per_launch": "all remaining units (the whole layer in one launch pair)" if upl == q.UINT32_MAX else upl,
                         "be_output_bit_identical_after_resume": identical_dev},
         "be_units_enqueued_at_arrival_mean": round(float(np.mean(waited_units)), 2) if waited_units else 0.0,
         "be_output_bit_identical_after_resume": identical,
@@ -493,6 +496,8 @@ def main() -> int:
                     help="LS-under-BE-load latency trials (Mixtral weights only; 0 = skip)")
     ap.add_argument("--units-per-call", type=int, default=4)
     ap.add_argument("--lookahead", type=int, default=1)
+    ap.add_argument("--units-per-launch", type=int, default=0,
+                    help="launch size of the enqueued, device-stopped BE sequence (0 = the whole layer at once)")
     ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 2, 4],
                     help="down_ksplit of the BE context in the latency scenario (0 = from the configuration)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -581,9 +586,9 @@ def main() -> int:
     mixtral = cfg.weight_seed == wl.CONFIGS["cfg2"].weight_seed and cfg.dtype == "bf16" and not mx and not args.rowmajor
     if args.latency_trials > 0 and mixtral:
         lat = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
-                         be_ksplit=args.be_ksplit)
+                         be_ksplit=args.be_ksplit, units_per_launch=args.units_per_launch)
         own = ls_latency(wl, q, torch, GpuLayer, dw, args.latency_trials, args.units_per_call, args.lookahead,
-                         be_ksplit=args.be_ksplit, ls_own_stream=True)
+                         be_ksplit=args.be_ksplit, ls_own_stream=True, units_per_launch=args.units_per_launch)
         lat["ls_on_own_stream"] = {"ls_latency_ms": own["ls_latency_ms"], "device_stop": own["device_stop"],
                                    "be_output_bit_identical_after_resume": own["be_output_bit_identical_after_resume"]}
         log("LS latency under BE load:", json.dumps(lat))

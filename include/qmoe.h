@@ -239,20 +239,26 @@ int32_t moe_expert_run(moe_ctx *ctx, const void *x, const moe_weights *w, uint32
 int32_t moe_expert_run_units(moe_ctx *ctx, const void *x, const moe_weights *w, const uint32_t *unit_ids,
                              uint32_t n, moe_cursor *cursor, void *stream);
 
-/* Expert work enqueued ahead and stopped from the device side (Discussion, Sec. 6, paragraph on
- * overlapping preemption with execution: named there as future work).  moe_expert_enqueue puts ALL units that have
- * not run yet on the stream, as launches of units_per_launch units each, and returns without waiting.
- * In front of every launch a one-thread gate kernel reads the context's stop word (host memory mapped
- * into the device): while it is clear the launch runs in full; once it is set, that launch and every
- * later one of the sequence do nothing.  No kernel waits or spins.  moe_expert_stop sets the stop word
- * (a plain host store; may be called from another thread than the one that enqueued).  Work of other
- * contexts may be enqueued on the stream at any time; it runs behind whatever the sequence still
- * executes (at most the launch in progress plus the empty shells of the rest).
- * moe_expert_collect waits for the stream (unless the device has already reported the whole sequence
- * complete), reads how many launches ran in full, books their units as
- * executed, clears the stop word and returns the cursor in *cursor ([host]); MOE_DONE if every unit
- * has run, MOE_OK otherwise (then carry on with moe_expert_enqueue or moe_expert_run).  A launch
- * either ran completely or not at all, and its arithmetic is that of moe_expert_run, bit for bit.
+/* Expert work enqueued ahead and stopped from the device side, at the granularity of a work unit
+ * (Discussion, Sec. 6, paragraph on overlapping preemption with execution: named there as future work).
+ * moe_expert_enqueue puts ALL units that have not run yet on the stream, as launches of
+ * units_per_launch units each, and returns without waiting.  moe_expert_stop sets the context's stop
+ * word (a plain store to host memory that is mapped into the device; it may come from another thread
+ * than the one that enqueued).  Every workgroup of the sequence looks at that word when it starts:
+ * once it is set, workgroups that have not started yet do nothing, so the sequence ends as soon as
+ * the workgroups in flight have finished their tiles (a fraction of one unit's duration), whatever
+ * units_per_launch is; the launches behind the stop are closed as a whole by a one-thread gate kernel
+ * in front of each.  No kernel waits or spins.  The workgroups count themselves per row range; a
+ * down-projection workgroup runs only if all gate-up workgroups of its rows ran, and a small kernel
+ * behind the last launch reports, per row range, whether all its down-projection workgroups ran.
+ * Work of other contexts may be enqueued on the stream at any time; it runs behind whatever the
+ * sequence still executes.
+ * moe_expert_collect waits for the stream, reads the report, books the units whose rows are all
+ * complete as executed (a unit whose rows were only partly computed when the stop took effect is
+ * not booked: it runs again, in full and to the same bits, when the batch resumes), clears the stop
+ * word and returns the cursor in *cursor ([host]); MOE_DONE if every unit has run, MOE_OK otherwise
+ * (then carry on with moe_expert_enqueue or moe_expert_run; units booked out of list order are
+ * skipped).  The arithmetic is that of moe_expert_run, bit for bit.
  * Between enqueue and collect every other call on the context fails with MOE_E_STATE. */
 int32_t moe_expert_enqueue(moe_ctx *ctx, const void *x, const moe_weights *w, uint32_t units_per_launch,
                            void *stream);

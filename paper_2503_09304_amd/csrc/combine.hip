@@ -108,23 +108,55 @@ __global__ __launch_bounds__(256) void clear_bytes(uint8_t *__restrict__ p, long
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = 0;
 }
 
-__global__ void gate_kernel(const int32_t *__restrict__ stop_host, int32_t *__restrict__ completed_host,
-                            int32_t *__restrict__ go, int g, int n_launches) {
+__global__ void gate_kernel(const int32_t *__restrict__ stop_host, int32_t *__restrict__ go, int g) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     const int prev_open = g == 0 ? 1 : go[g - 1];
-    if (g > 0 && prev_open) {
-        __hip_atomic_store(completed_host, g, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
-    if (g < n_launches) {
-        const int stop = __hip_atomic_load(stop_host, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        go[g] = (prev_open && stop == 0) ? 1 : 0;
-    }
+    const int stop = __hip_atomic_load(stop_host, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    go[g] = (prev_open && stop == 0) ? 1 : 0;
+}
+
+struct ReportArgs {
+    int n;
+    Seg seg[kMaxSegs];
+};
+
+__global__ __launch_bounds__(256) void report_ranges(const ReportArgs r, const int32_t *__restrict__ cnt_dn,
+                                                     int32_t *__restrict__ ok_host, int dtype, int H, int ksplit) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= r.n) return;
+    const Seg g = r.seg[i];
+    const int ok = cnt_dn[g.row0] == down_wgs_of_range(dtype, H, ksplit, g.rows) ? 1 : 0;
+    __hip_atomic_store(ok_host + i, ok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ __launch_bounds__(256) void clear_words(int32_t *__restrict__ p, long n) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = 0;
 }
 
 }  // namespace
 
-hipError_t launch_gate(const int32_t *stop_host, int32_t *completed_host, int32_t *go, int g, int n_launches, hipStream_t s) {
-    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, stop_host, completed_host, go, g, n_launches);
+hipError_t launch_gate(const int32_t *stop_host, int32_t *go, int g, hipStream_t s) {
+    hipLaunchKernelGGL(gate_kernel, dim3(1), dim3(64), 0, s, stop_host, go, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_report(const Seg *ranges, int n, const int32_t *cnt_dn, int32_t *ok_host, int dtype, int H, int ksplit,
+                         hipStream_t s) {
+    for (int i = 0; i < n; i += kMaxSegs) {
+        ReportArgs r{};
+        r.n = std::min(kMaxSegs, n - i);
+        std::copy(ranges + i, ranges + i + r.n, r.seg);
+        hipLaunchKernelGGL(report_ranges, dim3((r.n + 255) / 256), dim3(256), 0, s, r, cnt_dn, ok_host + i, dtype, H, ksplit);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_clear_words(int32_t *p, long n, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<long>((n + 255) / 256, 1024);
+    hipLaunchKernelGGL(clear_words, dim3(blocks), dim3(256), 0, s, p, n);
     return hipGetLastError();
 }
 

@@ -200,7 +200,9 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
     };
     { Scope sc(a.prof, MOE_PROF_GATE_UP, s); launch(true); }
 
+    const int gu_col_tiles = b.k.col_tiles;
     b.k = dn_in;
+    b.k.need = gu_col_tiles;         // gate-up workgroups per row range
     b.k.cw = 32;
     b.k.col_tiles = (a.H + 255) / 256;
     if (a.ksplit > 1 && a.partial != nullptr) {

@@ -94,6 +94,10 @@ struct BArgs {
 template <int T, bool GATEUP, int WF, bool STREAM, int D>
 __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, const int ct, const int kq, const int ksplit,
                                             const long plane, char *lds) {
+    // Stoppable launches: the workgroup leaves behind the prologue's barrier if the stop word is set or
+    // (down projection) the gate-up workgroups of its rows did not all run.
+    __shared__ int s_run;
+    const WgProbe probe = wg_probe(p, un.row0);
     constexpr int ROWS = T * 32;
     constexpr int STAGE = ROWS * 128;      // bytes of one LDS stage: 64 bf16 per row
     // The 7- and 8-tile variants are MFMA-bound: they keep three token-tile stages, write tile it+2
@@ -344,8 +348,10 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
         if constexpr (!P3 && j < DA) load_a(j, std::integral_constant<int, j % NA>{});
         load_b(j, std::integral_constant<int, j % NB>{});
     });
+    wg_decide(p, un.row0, 1, probe, &s_run);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    if (p.go != nullptr && s_run == 0) return;
     if constexpr (P3) read_af(0, std::integral_constant<int, 0>{});
     int it = 0;
     for (; it + U <= iters; it += U) {
@@ -474,7 +480,14 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     // two token-tile stages (three for the 7- and 8-tile variants); at least 8 KiB per wave for the
     // epilogue's store staging
     __shared__ __attribute__((aligned(16))) char lds[((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) > 32768 ? ((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) : 32768];
-    if (b.k.go != nullptr && *b.k.go == 0) return;      // a closed gate: this launch is skipped as a whole
+    // A closed gate: the sequence was stopped before this launch, or an earlier workgroup of it saw
+    // the stop word.  The word may change while the launch runs, so one thread reads it for all.
+    if (b.k.go != nullptr) {
+        __shared__ int s_go;
+        if (threadIdx.x == 0) s_go = __hip_atomic_load(b.k.go, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (s_go == 0) return;
+    }
     int ct, kq;
     moe_unit un;
     if (!map_block<STREAM>(b, un, ct, kq)) return;

@@ -13,7 +13,7 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 template <bool GATEUP>
 __global__ __launch_bounds__(256) void expert_f32(const KArgs p, int row_tiles) {
-    if (p.go != nullptr && *p.go == 0) return;
+    __shared__ int s_run;
     __shared__ float As[16][65];
     __shared__ float B0s[16][65];
     __shared__ float B1s[GATEUP ? 16 : 1][65];
@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void expert_f32(const KArgs p, int row_tiles) 
     const moe_unit un = p.units[p.u0 + ui];
     const int r0 = rt * 64;
     if (r0 >= un.rows) return;
+    if (!wg_may_run(p, un.row0, (un.rows + 63) >> 6, &s_run)) return;
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
     const float *b0 = (const float *)p.b0 + (long)un.expert * p.b_estride;
     const float *b1 = GATEUP ? (const float *)p.b1 + (long)un.expert * p.b_estride : nullptr;
@@ -93,6 +94,7 @@ void launch_experts_f32(const ExpertArgs &a, const KArgs &gu_in, const KArgs &dn
     const int row_tiles = (a.max_rows + 63) / 64;
     gu.col_tiles = (a.F + 63) / 64;
     dn.col_tiles = (a.H + 63) / 64;
+    dn.need = gu.col_tiles;          // gate-up workgroups per 64-row tile
     { Scope sc(a.prof, MOE_PROF_GATE_UP, s);
       hipLaunchKernelGGL(expert_f32<true>, dim3(a.nu * row_tiles * gu.col_tiles), dim3(256), 0, s, gu, row_tiles); }
     { Scope sc(a.prof, MOE_PROF_DOWN, s);

@@ -59,7 +59,7 @@ bool config_ok(const moe_config *c, const char **why) {
 
 // Offsets of the workspace regions, computed the same way for sizing and for carving.
 struct Layout {
-    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, go, units, wgt, act, out, partial, total;
+    size_t logits, topk_idx, topk_w, cnt, off, n_units, perm, inv, rank, blockoff, cls, done, go, prog, units, wgt, act, out, partial, total;
     bool has_partial;
     int ksplit;            // 1, 2 or 4: K ranges of the down projection, one partial plane each
     uint32_t max_units;
@@ -98,6 +98,7 @@ Layout make_layout(const moe_config &c) {
     L.cls = take(N ? N : 1);
     L.done = take(A ? A : 1);           // completion flag per sorted row (moe_combine_complete)
     L.go = take(((size_t)L.max_units + 1) * 4);   // gate words of an enqueued launch sequence
+    L.prog = take((A ? 2 * A : 1) * 4);           // its progress: workgroups that ran per row range, gate-up [A] then down [A]
     L.units = take((size_t)L.max_units * sizeof(moe_unit));
     L.wgt = take(((E + 15) / 16 * 16) * (size_t)c.H * 2);
     L.act = take(A * (size_t)c.F * es);
@@ -139,10 +140,12 @@ struct moe_ctx {
     hipStream_t last_stream;                   // stream of the last expert launch (moe_get adds the planes there)
     bool done_valid;                           // the device flags of this layer-batch have been cleared
     bool pending;                              // an enqueued launch sequence has not been collected yet
-    std::vector<std::vector<uint32_t>> plan;   // the units of each launch of that sequence
+    std::vector<uint32_t> plan;                // the units of that sequence
+    std::vector<qmoe::Seg> plan_ranges;        // the row ranges its launches worked on, in the order of the device's report
     std::vector<int32_t> cnt;
-    int32_t *pinned;  // 2E counts, unit count, sequence word, stop word, completed-launch count: pinned host memory mapped into the device
-                      // (allocated at first route); the permutation kernels write it directly
+    int32_t *pinned;  // 2E counts, unit count, sequence word, stop word, a spare word, then one completion flag per row
+                      // range of an enqueued sequence (at most max_units): pinned host memory mapped into the device
+                      // (allocated at first route); the permutation and report kernels write it directly
     int32_t *pinned_dev;   // the device's address of the same memory
     int32_t seq;           // sequence number of the last report asked for
     int spin_ms;           // how long moe_permute polls for the report before it waits for the stream
@@ -295,7 +298,7 @@ int32_t moe_route(moe_ctx *ctx, const void *x, int32_t n_tokens, const moe_weigh
     if (w->layout == MOE_W_MXFP4 && (!w->S1 || !w->S3 || !w->S2)) return fail(MOE_E_ARG, "moe_route: 4-bit weights need the scale pointers S1, S3, S2");
     if (n_tokens > 0 && !x) return fail(MOE_E_ARG, "moe_route: null x");
     if (!ctx->pinned) {
-        const size_t words = 2 * (size_t)ctx->cfg.E + 4;   // counts, unit count, sequence word, stop word, completed launches
+        const size_t words = 2 * (size_t)ctx->cfg.E + 4 + ctx->lay.max_units;   // counts, unit count, sequence word, stop word, spare, range flags
         hipError_t e = hipHostMalloc((void **)&ctx->pinned, words * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent);
         if (e != hipSuccess) { ctx->pinned = nullptr; return hip_fail(e, "moe_route: hipHostMalloc"); }
         e = hipHostGetDevicePointer((void **)&ctx->pinned_dev, ctx->pinned, 0);
@@ -407,13 +410,20 @@ int32_t moe_permute(moe_ctx *ctx, const uint8_t *prio, moe_cursor *cursor, void 
 }
 
 // Launches the expert kernels for the listed units (already validated: in range, distinct, not
-// yet executed); go: gate word of the launch on the device, or nullptr.
+// yet executed).  go: gate word of the launch on the device for a launch of an enqueued, stoppable
+// sequence (its workgroups then also watch the stop word and count themselves per row range), or
+// nullptr.  ranges (may be null) receives the row ranges the launches work on.
 static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
-                                const int32_t *go, hipStream_t stream, const char *who) {
+                                int32_t *go, std::vector<qmoe::Seg> *ranges, hipStream_t stream, const char *who) {
     if (ids.empty()) return MOE_OK;
     ctx->last_stream = stream;
     qmoe::ExpertArgs a{};
     a.go = go;
+    if (go != nullptr) {
+        a.stop = ctx->pinned_dev + 2 * ctx->cfg.E + 2;
+        a.cnt_gu = at<int32_t>(ctx, ctx->lay.prog);
+        a.cnt_dn = a.cnt_gu + (size_t)ctx->N * ctx->cfg.k;
+    }
     a.x = x; a.W1 = w->W1; a.W3 = w->W3; a.W2 = w->W2;
     a.perm = at<int32_t>(ctx, ctx->lay.perm);
     a.units = at<moe_unit>(ctx, ctx->lay.units);
@@ -469,12 +479,15 @@ static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *
         }
         if (segs.size() > (size_t)qmoe::kMaxSegs && contiguous) {
             // too many segments for the kernel arguments: the launch reads the device unit list
+            if (ranges)
+                for (uint32_t i : ids) ranges->push_back(qmoe::Seg{(uint32_t)un[i].row0, (uint16_t)un[i].rows, (uint16_t)un[i].expert});
             a.u0 = ids.front(); a.nu = (uint32_t)ids.size();
             a.max_rows = 0;
             for (uint32_t i : ids) a.max_rows = std::max(a.max_rows, (int)un[i].rows);
             a.segs = nullptr; a.nseg = 0;
             e = qmoe::launch_experts(a, stream);
         } else {
+            if (ranges) ranges->insert(ranges->end(), segs.begin(), segs.end());
             for (size_t s0 = 0; s0 < segs.size() && e == hipSuccess; s0 += qmoe::kMaxSegs) {
                 const size_t cnt = std::min(segs.size() - s0, (size_t)qmoe::kMaxSegs);
                 a.segs = segs.data() + s0; a.nseg = (int)cnt;
@@ -486,6 +499,8 @@ static int32_t launch_unit_list(moe_ctx *ctx, const void *x, const moe_weights *
         }
     } else {
         // fp32 kernels walk ranges of the device unit list: one launch per run of consecutive ids
+        if (ranges)
+            for (uint32_t i : ids) ranges->push_back(qmoe::Seg{(uint32_t)un[i].row0, (uint16_t)un[i].rows, (uint16_t)un[i].expert});
         for (size_t i = 0; i < ids.size() && e == hipSuccess;) {
             size_t j = i + 1;
             while (j < ids.size() && ids[j] == ids[j - 1] + 1) ++j;
@@ -515,7 +530,7 @@ static void book_units(moe_ctx *ctx, const std::vector<uint32_t> &ids) {
 
 static int32_t run_unit_list(moe_ctx *ctx, const void *x, const moe_weights *w, const std::vector<uint32_t> &ids,
                              hipStream_t stream, const char *who) {
-    const int32_t rc = launch_unit_list(ctx, x, w, ids, nullptr, stream, who);
+    const int32_t rc = launch_unit_list(ctx, x, w, ids, nullptr, nullptr, stream, who);
     if (rc == MOE_OK) book_units(ctx, ids);
     return rc;
 }
@@ -572,30 +587,40 @@ int32_t moe_expert_enqueue(moe_ctx *ctx, const void *x, const moe_weights *w, ui
     if (rc != MOE_OK) return rc;
     if (units_per_launch == 0) return fail(MOE_E_ARG, "moe_expert_enqueue: units_per_launch must be at least 1");
     hipStream_t s = (hipStream_t)stream;
-    ctx->plan.clear();
+    std::vector<std::vector<uint32_t>> groups;
     for (uint32_t u = ctx->next_unit; u < ctx->n_units; ++u) {
         if (ctx->executed[u]) continue;
-        if (ctx->plan.empty() || ctx->plan.back().size() >= units_per_launch) ctx->plan.emplace_back();
-        ctx->plan.back().push_back(u);
+        if (groups.empty() || groups.back().size() >= units_per_launch) groups.emplace_back();
+        groups.back().push_back(u);
     }
-    if (ctx->plan.empty()) return MOE_DONE;
+    if (groups.empty()) return MOE_DONE;
     const int E = ctx->cfg.E;
-    int32_t *stop = ctx->pinned + 2 * E + 2, *completed = ctx->pinned + 2 * E + 3;
-    *stop = 0;
-    *completed = 0;
-    std::atomic_thread_fence(std::memory_order_seq_cst);
+    // No kernel of an earlier sequence is left (it was collected): clear the range flags the report
+    // kernel will set, so that a sequence cut short by an error reports nothing, and the stop word.
+    memset(ctx->pinned + 2 * E + 4, 0, (size_t)ctx->lay.max_units * sizeof(int32_t));
+    __atomic_store_n(ctx->pinned + 2 * E + 2, 0, __ATOMIC_SEQ_CST);
     const int32_t *stop_dev = ctx->pinned_dev + 2 * E + 2;
-    int32_t *completed_dev = ctx->pinned_dev + 2 * E + 3;
     int32_t *go = at<int32_t>(ctx, ctx->lay.go);
-    const int n = (int)ctx->plan.size();
+    ctx->plan.clear();
+    ctx->plan_ranges.clear();
     ctx->pending = true;     // from here on the stream holds launches that read this context's state
-    for (int g = 0; g <= n; ++g) {
-        hipError_t e = qmoe::launch_gate(stop_dev, completed_dev, go, g, n, s);
+    // the progress counters of the row ranges start at zero (a fill kernel: the call may be captured)
+    hipError_t e = qmoe::launch_clear_words(at<int32_t>(ctx, ctx->lay.prog), 2 * (long)ctx->N * ctx->cfg.k, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_expert_enqueue: clearing the counters");
+    for (size_t g = 0; g < groups.size(); ++g) {
+        e = qmoe::launch_gate(stop_dev, go, (int)g, s);
         if (e != hipSuccess) return hip_fail(e, "moe_expert_enqueue: gate");
-        if (g == n) break;
-        rc = launch_unit_list(ctx, x, w, ctx->plan[g], go + g, s, "moe_expert_enqueue: launch");
+        rc = launch_unit_list(ctx, x, w, groups[g], go + g, &ctx->plan_ranges, s, "moe_expert_enqueue: launch");
         if (rc != MOE_OK) return rc;
+        ctx->plan.insert(ctx->plan.end(), groups[g].begin(), groups[g].end());
     }
+    if (ctx->plan_ranges.size() > ctx->lay.max_units)
+        return fail(MOE_E_HIP, "moe_expert_enqueue: %zu row ranges exceed the bound %u", ctx->plan_ranges.size(), ctx->lay.max_units);
+    // behind the last launch: which row ranges are complete, written to host memory
+    e = qmoe::launch_report(ctx->plan_ranges.data(), (int)ctx->plan_ranges.size(),
+                            at<int32_t>(ctx, ctx->lay.prog) + (size_t)ctx->N * ctx->cfg.k,
+                            ctx->pinned_dev + 2 * E + 4, ctx->cfg.dtype, ctx->cfg.H, ctx->lay.ksplit, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_expert_enqueue: report");
     return MOE_OK;
 }
 
@@ -611,19 +636,28 @@ int32_t moe_expert_collect(moe_ctx *ctx, moe_cursor *cursor, void *stream) {
     if (!cursor) return fail(MOE_E_ARG, "moe_expert_collect: null cursor");
     if (ctx->state != ST_PERMUTED) return fail(MOE_E_STATE, "moe_expert_collect: call moe_permute first");
     if (ctx->pending) {
-        // If the last gate has already reported every launch complete there is nothing to wait for;
-        // otherwise the count is final only once the stream has drained.
-        volatile int32_t *word = ctx->pinned + 2 * ctx->cfg.E + 3;
-        if ((size_t)*word != ctx->plan.size()) {
-            hipError_t e = hipStreamSynchronize((hipStream_t)stream);
-            if (e != hipSuccess) return hip_fail(e, "moe_expert_collect: waiting for the stream");
-        }
+        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, "moe_expert_collect: waiting for the stream");
         std::atomic_thread_fence(std::memory_order_acquire);
-        const int32_t completed = *word;
-        if (completed < 0 || (size_t)completed > ctx->plan.size())
-            return fail(MOE_E_HIP, "moe_expert_collect: the device reports %d completed launches of %zu", completed, ctx->plan.size());
-        for (int32_t g = 0; g < completed; ++g) book_units(ctx, ctx->plan[g]);
+        // A unit has run when every row range that overlaps it is complete.  Ranges are disjoint, so a
+        // table over the sorted rows of the sequence decides it.
+        const volatile int32_t *ok = ctx->pinned + 2 * ctx->cfg.E + 4;
+        std::vector<uint8_t> row_ok((size_t)ctx->N * ctx->cfg.k, 0);
+        for (size_t i = 0; i < ctx->plan_ranges.size(); ++i) {
+            const int32_t v = ok[i];
+            if (v != 0 && v != 1) return fail(MOE_E_HIP, "moe_expert_collect: the device reports %d for row range %zu", v, i);
+            if (v) std::fill(row_ok.begin() + ctx->plan_ranges[i].row0, row_ok.begin() + ctx->plan_ranges[i].row0 + ctx->plan_ranges[i].rows, 1);
+        }
+        std::vector<uint32_t> ran;
+        for (uint32_t u : ctx->plan) {
+            const moe_unit &un = ctx->units[u];
+            bool all = true;
+            for (int32_t r = un.row0; r < un.row0 + un.rows && all; ++r) all = row_ok[(size_t)r] != 0;
+            if (all) ran.push_back(u);
+        }
+        book_units(ctx, ran);
         ctx->plan.clear();
+        ctx->plan_ranges.clear();
         ctx->pending = false;
         __atomic_store_n(ctx->pinned + 2 * ctx->cfg.E + 2, 0, __ATOMIC_SEQ_CST);
     }

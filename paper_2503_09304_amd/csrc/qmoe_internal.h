@@ -94,8 +94,17 @@ struct ExpertArgs {
     float *partial;             // [ksplit][A][H] fp32 partial planes of the K-split down projection, or nullptr
                                 // (they stay as they are: moe_combine adds them, launch_reduce_planes on request)
     long plane;                 // elements per plane
-    const int32_t *go;          // gate word of this launch on the device, or nullptr (see launch_gate)
+    // launches of an enqueued, stoppable sequence (all nullptr otherwise; see launch_gate, launch_report)
+    int32_t *go;                // [device] gate word of this launch
+    const int32_t *stop;        // [host, mapped] the context's stop word
+    int32_t *cnt_gu, *cnt_dn;   // [device] workgroups that ran per row range (indexed by first sorted row): gate-up, down
 };
+
+// Workgroups of the down projection that cover a row range of `rows` rows: what its counter reads
+// when the range is complete.
+__host__ __device__ inline int down_wgs_of_range(int dtype, int H, int ksplit, int rows) {
+    return dtype == MOE_BF16 ? ((H + 255) / 256) * ksplit : ((H + 63) / 64) * ((rows + 63) / 64);
+}
 hipError_t launch_experts(const ExpertArgs &a, hipStream_t s);
 
 // out[r,:] = ((p0 + p1) + p2) + p3 (p0 + p1 with two planes) for the rows of the segments: what
@@ -123,10 +132,15 @@ struct CombineArgs {
     int N, H, k, dtype, class_mask;
 };
 hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
-// Gate between the launches of an enqueued sequence (moe_expert_enqueue): one thread.  If commit != 0
-// and go[g-1] is set, launch g-1 ran in full: *completed (host memory) = g.  Then, if g < n_launches,
-// go[g] = (g == 0 || go[g-1]) && *stop == 0: once a gate closes, every later one stays closed.
-hipError_t launch_gate(const int32_t *stop_host, int32_t *completed_host, int32_t *go, int g, int n_launches, hipStream_t s);
+// Gate in front of launch g of an enqueued sequence (moe_expert_enqueue): one thread,
+// go[g] = (g == 0 || go[g-1]) && *stop == 0.  Once a gate closes every later one stays closed, so the
+// workgroups of the launches behind a stop leave after one read of device memory.
+hipError_t launch_gate(const int32_t *stop_host, int32_t *go, int g, hipStream_t s);
+// Behind the last launch of the sequence: ok_host[i] (host memory, mapped) = 1 if all `need(rows)`
+// down-projection workgroups of row range i ran (cnt_dn[row0] == down_wgs_of_range), else 0.
+hipError_t launch_report(const Seg *ranges, int n, const int32_t *cnt_dn, int32_t *ok_host, int dtype, int H, int ksplit,
+                         hipStream_t s);
+hipError_t launch_clear_words(int32_t *p, long n, hipStream_t s);
 // Completion flags per sorted row (used by moe_combine_complete): clear all, set the rows of segments.
 hipError_t launch_clear_done(uint8_t *done, long n, hipStream_t s);
 hipError_t launch_mark_done(const Seg *segs, int n, uint8_t *done, hipStream_t s);

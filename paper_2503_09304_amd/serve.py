@@ -79,10 +79,11 @@ class _Slot:
 class Engine:
     def __init__(self, weights: q.MoeWeights, glue, E: int, k: int, H: int, F: int, layers: int, batch_size: int,
                  max_prompt: int, preemptive: bool, units_per_call: int = 4, lookahead: int = 1, chunk_rows: int = 256,
-                 device_stop: bool = True, device="cuda:0"):
+                 device_stop: bool = True, units_per_launch: int = q.UINT32_MAX, device="cuda:0"):
         self.w, self.layers, self.batch_size, self.max_prompt = weights, layers, batch_size, max_prompt
         self.preemptive, self.units_per_call, self.lookahead = preemptive, units_per_call, lookahead
         self.device_stop = device_stop
+        self.units_per_launch = units_per_launch     # enqueued (device-stopped) layers: launch size; default the whole layer
         self.device = device
         self.glue = glue
         self.bank_rows = glue.bank_rows
@@ -150,7 +151,7 @@ class Engine:
             elif self.device_stop and stage == q.SCHED_PREFILL:
                 # the whole layer goes on the stream as gated launches; the loop watches for an LS
                 # prompt meanwhile and closes the gates when one waits
-                rc = ctx.expert_enqueue(x, self.w, self.units_per_call)
+                rc = ctx.expert_enqueue(x, self.w, self.units_per_launch)
                 while rc != q.MOE_DONE:
                     ev = torch.cuda.Event()
                     ev.record()
@@ -167,7 +168,7 @@ class Engine:
                             break
                     rc = ctx.expert_collect()
                     if rc != q.MOE_DONE:
-                        rc = ctx.expert_enqueue(x, self.w, self.units_per_call)
+                        rc = ctx.expert_enqueue(x, self.w, self.units_per_launch)
             else:
                 pending, done = [], False
                 while not done:
