@@ -27,8 +27,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2030989674, "cfg4": 1920201172, "cfg3_be": 3279625939, "cfg5": 2093874789,
-                          "cfg4_mxfp4": 516047793, "cfg3_be_mxfp4": 1541557747}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2032283507, "cfg4": 1919675526, "cfg3_be": 3273875430, "cfg5": 2659429119,
+                          "cfg4_mxfp4": 515344980, "cfg3_be_mxfp4": 1775656828}
 
 
 def log(*a):
@@ -78,9 +78,10 @@ def expert_boundaries(units):
 
 
 def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
-    """Times one workload: K steps between two synchronisations with nothing else on the stream (the
-    figure of record), then the same loop again with HIP events around the gate-up launches, again
-    around the down launches, per stage, and per step."""
+    """Times one workload.  Order: W warm-up steps; K steps with HIP events around the gate-up launches and
+    K with events around the down launches (per-kernel times); then the timed region, K steps between
+    two synchronisations with nothing else on the stream (the figure of record); then per-stage and
+    per-step event timings."""
     import numpy as np
     import torch
 
@@ -105,7 +106,21 @@ def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
         step()
     torch.cuda.synchronize()
     counts = g.ctx.get("counts").cpu().numpy()
-    # ---- timed region: K steps, no event on the stream
+    # ---- per-kernel times first: the same K steps with the gate-up launches bracketed by events on the launch
+    # stream, then with the down launches bracketed (these loops also bring the chip to its steady clocks, which a
+    # few warm-up steps of half a millisecond do not: the gate-up loop is therefore run twice, before and after the
+    # down loop, and both averages are reported)
+    prof = {}
+    for tag, kinds in (("gate_up_first_loop", ["gate_up"]), ("down", ["down"]), ("gate_up", ["gate_up"])):
+        g.ctx.profile(kinds)
+        g.ctx.profile_read()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        prof[tag] = g.ctx.profile_read()[kinds[0]]
+    g.ctx.profile(False)
+
+    # ---- timed region (the figure of record): K steps, no event on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -114,17 +129,6 @@ def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / steps
     tokens_per_s = cfg.N / (ms_per_step * 1e-3)
-    # ---- the same loop with the gate-up launches bracketed by events on the launch stream, then the down launches
-    prof = {}
-    for kinds in (["gate_up"], ["down"]):
-        g.ctx.profile(kinds)
-        g.ctx.profile_read()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        prof.update({k: v for k, v in g.ctx.profile_read().items() if k in kinds})
-    g.ctx.profile(False)
-
     # ---- per-stage times
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
     acc = [0.0] * 4
@@ -203,7 +207,10 @@ def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name + ("_mxfp4" if mx else "")) if not rowmajor else None
     roof.update({"kernel": "expert_bf16 gate-up (W1,W3 GEMM + SwiGLU)", "avg_launch_ms": round(gu_avg_ms, 4),
                  "launches": gu_n, "timed_by": "HIP events on the launch stream around every gate-up launch, in a loop "
-                                               "of the same K steps run right after the timed region",
+                                               "of the same K steps run right before the timed region (the third such loop; "
+                                               "the first, run straight after the W warm-up steps while the clocks still "
+                                               "settle, is avg_launch_ms_first_loop)",
+                 "avg_launch_ms_first_loop": round(prof["gate_up_first_loop"][0] / max(prof["gate_up_first_loop"][1], 1), 4),
                  "algorithmic_bytes_per_launch": int(gub),
                  "algorithmic_flops_per_launch": gu_flops,
                  "down_avg_launch_ms": round(dn_avg_ms, 4),
@@ -487,6 +494,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ls-first", action="store_true", help="skip the LS-phase-first measurement (profiling runs)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the sub-records of cfg4, cfg3_be and cfg5 that the default (cfg2) run adds")
     ap.add_argument("--rowmajor", action="store_true", help="keep the weights row-major (default: packed at load)")
@@ -500,6 +508,8 @@ def main() -> int:
                     help="launch size of the enqueued, device-stopped BE sequence (0 = the whole layer at once)")
     ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 2, 4],
                     help="down_ksplit of the BE context in the latency scenario (0 = from the configuration)")
+    ap.add_argument("--calib-mfma", action="store_true",
+                    help="also launch the register-only MFMA loop, the yardstick for MFMA-busy and clock counters")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy, the yardstick for HBM byte counters")
     args = ap.parse_args()
@@ -547,6 +557,24 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.calib_mfma and cfg.dtype == "bf16" and not mx:
+        # yardstick for the MFMA counters: the register-only MFMA loop on the workload's own x and W1 bits,
+        # one workgroup (4 waves, one per SIMD) per compute unit
+        xs = torch.from_numpy(inp.x.view(np.int16)).to("cuda:0")
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        for wgs in (cus, 2 * cus):
+            for rep in range(3):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                q.moe_probe_mfma(xs, dw.W1, 20000, wgs, sink)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b)
+                log(f"mfma probe: {wgs} workgroups x 4 waves x 20000 x 8 MFMAs in {ms:.3f} ms = "
+                    f"{wgs * 4 * 20000 * 8 * 32768 / ms / 1e9:.1f} TFLOP/s")
+        del xs, sink
+
     m = measure(cfg, inp, dw, args.steps, args.warmup, mx, args.rowmajor)
     g = m.pop("_layer")
     ms_per_step = m["ms_per_step"]
@@ -555,7 +583,7 @@ def main() -> int:
     # rows combined, then every BE unit): two passes over the weights of experts that hold both classes
     ls_first = None
     n_ls_units = sum(1 for u in g.ctx.units() if u[1] == 0)
-    if 0 < n_ls_units < g.ctx.cursor.n_units:
+    if 0 < n_ls_units < g.ctx.cursor.n_units and not args.no_ls_first:
         counts = g.ctx.get("counts").cpu().numpy()
         t_ls, t_all = [], []
         for _ in range(10):

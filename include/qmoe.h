@@ -315,6 +315,14 @@ enum { MOE_PROF_GATE_UP = 0, MOE_PROF_DOWN = 1, MOE_PROF_DOWN_REDUCE = 2 /* unus
 int32_t moe_profile(moe_ctx *ctx, int32_t kinds);
 int32_t moe_profile_read(moe_ctx *ctx, float *ms, uint32_t *launches);
 
+/* Yardstick for profiles of the MFMA-bound kernels (no part of the method): one launch of `workgroups`
+ * workgroups of 4 waves, each wave running iters * 8 bf16 MFMAs (32x32x16, 32768 flop each) on
+ * register operands taken once from a_bf16 and b_bf16 ([device], at least 4096 bf16 each, e.g. the
+ * first rows of x and of W1, so that the operands carry the workload's bit patterns); no memory
+ * traffic inside the loop.  sink: [device] one float (never written in practice).
+ * flop = workgroups * 4 * iters * 8 * 32768. */
+int32_t moe_probe_mfma(const void *a_bf16, const void *b_bf16, int32_t iters, int32_t workgroups, float *sink, void *stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *moe_last_error(void);
 

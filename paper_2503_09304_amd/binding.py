@@ -68,6 +68,11 @@ def moe_route_noalloc(cfg: "MoeConfig", x, n_tokens: int, Wg, bias, logits, topk
     return _check(rc)
 
 
+def moe_probe_mfma(a, b, iters: int, workgroups: int, sink) -> int:
+    """The register-only MFMA loop (a profiling yardstick, see include/qmoe.h)."""
+    return _check(lib().moe_probe_mfma(_ptr(a), _ptr(b), iters, workgroups, _ptr(sink), _stream()))
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -84,6 +89,7 @@ def lib():
         L.moe_workspace_bytes.argtypes = [C.POINTER(MoeConfig)]
         L.moe_create.argtypes = [C.POINTER(MoeConfig), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
         L.moe_destroy.argtypes = [C.c_void_p]
+        L.moe_probe_mfma.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.moe_route_noalloc.argtypes = [C.POINTER(MoeConfig), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
         L.moe_route.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(MoeWeights), C.c_void_p, C.c_void_p]
