@@ -508,6 +508,8 @@ def main() -> int:
                     help="launch size of the enqueued, device-stopped BE sequence (0 = the whole layer at once)")
     ap.add_argument("--be-ksplit", type=int, default=4, choices=[0, 1, 2, 4],
                     help="down_ksplit of the BE context in the latency scenario (0 = from the configuration)")
+    ap.add_argument("--calib-gemm", action="store_true",
+                    help="also time torch.matmul (the vendor GEMM library) on dense GEMMs of the gate-up shape: a yardstick")
     ap.add_argument("--calib-mfma", action="store_true",
                     help="also launch the register-only MFMA loop, the yardstick for MFMA-busy and clock counters")
     ap.add_argument("--calib-copy", action="store_true",
@@ -574,6 +576,26 @@ def main() -> int:
                 log(f"mfma probe: {wgs} workgroups x 4 waves x 20000 x 8 MFMAs in {ms:.3f} ms = "
                     f"{wgs * 4 * 20000 * 8 * 32768 / ms / 1e9:.1f} TFLOP/s")
         del xs, sink
+
+    if args.calib_gemm and cfg.dtype == "bf16":
+        # yardstick: the vendor library (whatever torch.matmul dispatches to) on dense GEMMs of the gate-up shape,
+        # random operands of the workload's distributions; no gather, no SwiGLU, no ragged segments
+        rows = cfg.A // cfg.E // 32 * 32
+        for name, a_shape, b_shape in (("one dense GEMM [A,H] x [H,2F]", (cfg.A, cfg.H), (cfg.H, 2 * cfg.F)),
+                                        ("batched over experts [E,A/E,H] x [E,H,2F]", (cfg.E, rows, cfg.H), (cfg.E, cfg.H, 2 * cfg.F))):
+            ta = torch.randn(a_shape, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+            tb = (torch.randn(b_shape, device="cuda:0", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            flop = 2.0 * ta.numel() * b_shape[-1]
+            for _ in range(5):
+                torch.matmul(ta, tb)
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for e0, e1 in ev:
+                e0.record(); torch.matmul(ta, tb); e1.record()
+            torch.cuda.synchronize()
+            ts = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+            log(f"vendor GEMM yardstick, {name}: median {ts[10]:.3f} ms = {flop / ts[10] / 1e9:.0f} TFLOP/s, best {flop / ts[0] / 1e9:.0f}")
+            del ta, tb
 
     m = measure(cfg, inp, dw, args.steps, args.warmup, mx, args.rowmajor)
     g = m.pop("_layer")
