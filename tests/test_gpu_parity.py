@@ -26,7 +26,7 @@ def say(*a):
     print(*a, flush=True)
 
 
-def check_values(cfg, lay, g, y_bits):
+def check_values(cfg, lay, g, y_bits, label=None):
     """Expert outputs and y of the device against the oracle layer `lay` (run here in full), every
     element.  fp32: max|err|/RMS <= 1e-4.  bf16 (bars: gpu_util): global 2e-2, per-element bar and RMS
     gate on the expert outputs and on the unrounded fp32 y; the bf16 y must be exactly that fp32 y
@@ -55,8 +55,9 @@ def check_values(cfg, lay, g, y_bits):
     r32 = check_bf16_expert_out(y32, y_ref, sig_y)
     ry = check_bf16_y(y_got, y_ref, sig_y)
     y_rounded = wl.as_f64(wl.f32_to_bf16_bits(np.asarray(y_ref, dtype=np.float32)))
-    lines = [f"{cfg.name} expert_out: {fmt(ro)}", f"{cfg.name} y (fp32):   {fmt(r32)}",
-             f"{cfg.name} y (bf16):   {fmt(ry)}  [rounding the exact y to bf16 alone: {rel_err(y_rounded, y_ref):.2e}]"]
+    name = label or cfg.name
+    lines = [f"{name} expert_out: {fmt(ro)}", f"{name} y (fp32):   {fmt(r32)}",
+             f"{name} y (bf16):   {fmt(ry)}  [rounding the exact y to bf16 alone: {rel_err(y_rounded, y_ref):.2e}]"]
     for ln in lines:
         say("  " + ln)
     if cfg.name in wl.CONFIGS:

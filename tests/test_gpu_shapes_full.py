@@ -106,8 +106,7 @@ def test_cfg4_decode_with_4bit_weights_full_size():
     r = g.fetch("logits", "topk_idx", "counts", "perm", "y")
     lay = oracle.OracleLayer(inp.x, inp.w, inp.prio, inp.bias, cfg.k, cfg.chunk_rows, logits=r["logits"].astype(np.float64))
     assert np.array_equal(r["topk_idx"], lay.idx) and np.array_equal(r["counts"], lay.cnt) and np.array_equal(r["perm"], lay.perm)
-    say("  cfg4 with 4-bit weights:")
-    check_values(cfg, lay, g, r["y"])
+    check_values(cfg, lay, g, r["y"], label="cfg4, 4-bit weights")
     nu = g.ctx.cursor.n_units
     h = GpuLayer(inp, mx, down_ksplit=4).full(tuple(range(1, nu)))
     assert torch.equal(bits(h.y), bits(g.y))
