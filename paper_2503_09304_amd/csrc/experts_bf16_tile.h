@@ -51,6 +51,12 @@ namespace bf16k {
 // MFMA-ordered blocks, turned into bf16 operands in registers (exactly: every such value is a bf16).
 enum { WF_ROWMAJOR = 0, WF_PACKED = 1, WF_MXFP4 = 2 };
 
+// Smallest number of token tiles whose variant keeps three LDS stages (see P3 in expert_tile).
+#ifndef QMOE_P3_MIN_T
+#define QMOE_P3_MIN_T 4
+#endif
+constexpr int kP3MinT = QMOE_P3_MIN_T;
+
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -100,10 +106,12 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
     const WgProbe probe = wg_probe(p, un.row0);
     constexpr int ROWS = T * 32;
     constexpr int STAGE = ROWS * 128;      // bytes of one LDS stage: 64 bf16 per row
-    // The 7- and 8-tile variants are MFMA-bound: they keep three token-tile stages, write tile it+2
-    // during iteration it, and so may read the first fragments of tile it+1 before the iteration's
-    // barrier; the LDS latency after the barrier disappears from the MFMA stream.
-    constexpr bool P3 = T >= 7;
+    // The variants of 4 and more token tiles keep three token-tile stages, write tile it+2 during
+    // iteration it, and so may read the first fragments of tile it+1 before the iteration's barrier;
+    // the LDS latency after the barrier disappears from the MFMA stream (8 tiles: -1.7 % on the
+    // 3584-token prefill; 4-5 tiles: gate-up -1.2 % on the 512-token batch, measured against the
+    // two-stage form on one machine).  Below 4 tiles an iteration is bound by the weight stream alone.
+    constexpr bool P3 = T >= kP3MinT;
     // Output columns per wave.  Gate-up: 32, or fewer (p.cw, a multiple of 4) on launches whose
     // workgroup count would otherwise end in a partly filled round of the chip; the wave's MFMA rows
     // beyond p.cw repeat its last weight row and are dropped in the epilogue.
@@ -190,7 +198,7 @@ __device__ __forceinline__ void expert_tile(const KArgs &p, const moe_unit un, c
 
     // Register rings: weight fragments of iterations it .. it+D (NB sets), token pieces of
     // it+1 .. it+D (NA sets).  Ring positions are compile-time constants: the loop is unrolled NA*NB.
-    constexpr int DA = T >= 7 ? 1 : (T >= 5 && D > 2 ? 2 : D);   // token pieces: same distance, or less where registers are scarce
+    constexpr int DA = P3 ? 1 : (T >= 5 && D > 2 ? 2 : D);   // token pieces: same distance, or less where registers are scarce
     constexpr int NB = D + 1, NA = DA, U = (NB % NA == 0) ? NB : NA * NB;
     u32x4 a_reg[NA * T];
     bf16x8 b_reg[NB * 8];  // [set][k-step][n-tile]; MXFP4: set 0 only, the operands of the current iteration
@@ -477,9 +485,9 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
 // in L2.  Where segments share an expert's weights the hint is left off so that L2 serves the re-reads.
 template <int TCAP, bool GATEUP, int WF, bool STREAM>
 __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
-    // two token-tile stages (three for the 7- and 8-tile variants); at least 8 KiB per wave for the
+    // two token-tile stages (three from 4 token tiles on); at least 8 KiB per wave for the
     // epilogue's store staging
-    __shared__ __attribute__((aligned(16))) char lds[((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) > 32768 ? ((TCAP >= 8 ? 3 : 2) * TCAP * 32 * 128) : 32768];
+    __shared__ __attribute__((aligned(16))) char lds[((TCAP >= kP3MinT ? 3 : 2) * TCAP * 32 * 128) > 32768 ? ((TCAP >= kP3MinT ? 3 : 2) * TCAP * 32 * 128) : 32768];
     // A closed gate: the sequence was stopped before this launch, or an earlier workgroup of it saw
     // the stop word.  The word may change while the launch runs, so one thread reads it for all.
     if (b.k.go != nullptr) {
@@ -492,13 +500,13 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
     moe_unit un;
     if (!map_block<STREAM>(b, un, ct, kq)) return;
     const int t_cnt = (un.rows + 31) >> 5;
-    // Prefetch distance of the weights: 3 iterations where the register file allows it, 2 for the 7- and 8-tile
-    // and the 2-tile variants; the token pieces of the 5- and 6-tile variants stay 2 ahead.
+    // Prefetch distance of the weights: 2 iterations for the three-stage variants (their loop is unrolled by
+    // a multiple of 3) and the 2-tile variant, 3 for the 1-tile variant.
     if (TCAP >= 8 && t_cnt > 7) expert_tile<(TCAP >= 8 ? 8 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 8 && t_cnt > 6) expert_tile<(TCAP >= 8 ? 7 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 5 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
-    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 5) expert_tile<(TCAP >= 6 ? 6 : 1), GATEUP, WF, STREAM, (kP3MinT <= 6 ? 2 : 3)>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 6 && t_cnt > 4) expert_tile<(TCAP >= 6 ? 5 : 1), GATEUP, WF, STREAM, (kP3MinT <= 5 ? 2 : 3)>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
+    else if (TCAP >= 4 && t_cnt > 2) expert_tile<(TCAP >= 4 ? 4 : 1), GATEUP, WF, STREAM, (kP3MinT <= 4 ? 2 : 3)>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else if (TCAP >= 2 && t_cnt > 1) expert_tile<(TCAP >= 2 ? 2 : 1), GATEUP, WF, STREAM, 2>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
     else expert_tile<1, GATEUP, WF, STREAM, 3>(b.k, un, ct, kq, b.ksplit, b.plane, lds);
 }
