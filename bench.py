@@ -77,7 +77,7 @@ def expert_boundaries(units):
     return [i for i in range(1, len(units)) if units[i][0] != units[i - 1][0] or units[i][1] != units[i - 1][1]]
 
 
-def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
+def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0, down_ksplit=0):
     """Times one workload.  Order: W warm-up steps; K steps with HIP events around the gate-up launches and
     K with events around the down launches (per-kernel times); then the timed region, K steps between
     two synchronisations with nothing else on the stream (the figure of record); then per-stage and
@@ -93,7 +93,7 @@ def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0):
     # 4-bit weights on a decode-sized batch: a workgroup's K-iteration is bound by its conversions, two
     # workgroups share a CU, and four K ranges (512 workgroups, one round) beat the two the
     # configuration default would take (0.057-0.066 against 0.073 ms for the down projection).
-    force_ks = 4 if (mx and cfg.A <= 32 * cfg.E and cfg.F % 256 == 0) else 0
+    force_ks = down_ksplit or (4 if (mx and cfg.A <= 32 * cfg.E and cfg.F % 256 == 0) else 0)
     g = GpuLayer(inp, dw, down_ksplit=force_ks)
     torch.cuda.synchronize()
 
@@ -494,6 +494,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--cpu-sample-tokens", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--down-ksplit", type=int, default=0, choices=[0, 1, 2, 4],
+                    help="down_ksplit of the benchmarked context (0 = chosen from the configuration)")
     ap.add_argument("--no-ls-first", action="store_true", help="skip the LS-phase-first measurement (profiling runs)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the sub-records of cfg4, cfg3_be and cfg5 that the default (cfg2) run adds")
@@ -597,7 +599,7 @@ def main() -> int:
             log(f"vendor GEMM yardstick, {name}: median {ts[10]:.3f} ms = {flop / ts[10] / 1e9:.0f} TFLOP/s, best {flop / ts[0] / 1e9:.0f}")
             del ta, tb
 
-    m = measure(cfg, inp, dw, args.steps, args.warmup, mx, args.rowmajor)
+    m = measure(cfg, inp, dw, args.steps, args.warmup, mx, args.rowmajor, down_ksplit=args.down_ksplit)
     g = m.pop("_layer")
     ms_per_step = m["ms_per_step"]
 
