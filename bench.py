@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 # HBM bytes per launch of the gate-up kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # scaled by what the same counters read for a 1 GiB device copy (profiles/bench_<workload>.md).
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2032283507, "cfg4": 1919675526, "cfg3_be": 3273875430, "cfg5": 2659429119,
+MEASURED_TRAFFIC_BYTES = {"cfg2": 2032283507, "cfg4": 1919675526, "cfg3_be": 3263265902, "cfg5": 2658861615,
                           "cfg4_mxfp4": 515344980, "cfg3_be_mxfp4": 1775656828}
 
 
@@ -567,7 +567,9 @@ def main() -> int:
         xs = torch.from_numpy(inp.x.view(np.int16)).to("cuda:0")
         sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
         cus = torch.cuda.get_device_properties(0).multi_processor_count
-        for wgs in (cus, 2 * cus):
+        # the clock settles over the first tens of milliseconds of load: three launches to warm up, then
+        # one wave per SIMD, two waves per SIMD, and one wave per SIMD again
+        for label, wgs in (("warm-up", cus), ("1 wave/SIMD", cus), ("2 waves/SIMD", 2 * cus), ("1 wave/SIMD again", cus)):
             for rep in range(3):
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
@@ -575,7 +577,7 @@ def main() -> int:
                 b.record()
                 torch.cuda.synchronize()
                 ms = a.elapsed_time(b)
-                log(f"mfma probe: {wgs} workgroups x 4 waves x 20000 x 8 MFMAs in {ms:.3f} ms = "
+                log(f"mfma probe ({label}): {wgs} workgroups x 4 waves x 20000 x 8 MFMAs in {ms:.3f} ms = "
                     f"{wgs * 4 * 20000 * 8 * 32768 / ms / 1e9:.1f} TFLOP/s")
         del xs, sink
 
