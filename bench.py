@@ -95,6 +95,7 @@ def measure(cfg, inp, dw, steps, warmup, mx, rowmajor, cuts=0, down_ksplit=0):
     # configuration default would take (0.057-0.066 against 0.073 ms for the down projection).
     force_ks = down_ksplit or (4 if (mx and cfg.A <= 32 * cfg.E and cfg.F % 256 == 0) else 0)
     g = GpuLayer(inp, dw, down_ksplit=force_ks)
+    g.ctx.stream_handle = int(torch.cuda.current_stream().cuda_stream)     # one stream throughout: skip the per-call lookup
     torch.cuda.synchronize()
 
     def step():

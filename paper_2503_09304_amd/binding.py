@@ -178,7 +178,14 @@ def _stream() -> int:
 
 class Context:
     """One in-flight layer-batch: the opaque moe_ctx plus the torch tensor that backs its workspace.
-    Methods are the C calls with tensors in place of pointers."""
+    Methods are the C calls with tensors in place of pointers.  The stream of every call is PyTorch's
+    current stream, looked up at each call, unless `stream_handle` holds a hipStream_t value (an int):
+    a caller that stays on one stream sets it once and saves the lookup (a few microseconds per call)."""
+
+    stream_handle = None
+
+    def _stream(self) -> int:
+        return _stream() if self.stream_handle is None else self.stream_handle
 
     def __init__(self, E, k, H, F, dtype, chunk_rows, max_tokens, device="cuda:0", down_ksplit=0):
         import torch
@@ -199,7 +206,7 @@ class Context:
         if getattr(self, "h", None):
             if lib().moe_destroy(self.h) == MOE_E_STATE:
                 cur = MoeCursor(0, 0)
-                lib().moe_expert_collect(self.h, C.byref(cur), _stream())
+                lib().moe_expert_collect(self.h, C.byref(cur), self._stream())
                 lib().moe_destroy(self.h)
             self.h = None
 
@@ -215,33 +222,33 @@ class Context:
 
     def route(self, x, w: MoeWeights, bias=None, n_tokens=None):
         n = x.shape[0] if n_tokens is None else n_tokens
-        rc = _check(lib().moe_route(self.h, _ptr(x), n, C.byref(w), _ptr(bias), _stream()))
+        rc = _check(lib().moe_route(self.h, _ptr(x), n, C.byref(w), _ptr(bias), self._stream()))
         self.N, self._w = n, w
         return rc
 
     def permute(self, prio) -> MoeCursor:
         if prio is not None and prio.element_size() != 1:
             raise TypeError("prio must be a uint8 tensor (one byte per token)")
-        _check(lib().moe_permute(self.h, _ptr(prio), C.byref(self.cursor), _stream()))
+        _check(lib().moe_permute(self.h, _ptr(prio), C.byref(self.cursor), self._stream()))
         return self.cursor
 
     def expert_run(self, x, w: MoeWeights, max_units: int = UINT32_MAX, cursor: Optional[MoeCursor] = None) -> int:
         cur = self.cursor if cursor is None else cursor
-        return _check(lib().moe_expert_run(self.h, _ptr(x), C.byref(w), max_units, C.byref(cur), _stream()))
+        return _check(lib().moe_expert_run(self.h, _ptr(x), C.byref(w), max_units, C.byref(cur), self._stream()))
 
     def combine(self, y, class_mask: int = MOE_CLASS_ALL) -> int:
-        return _check(lib().moe_combine(self.h, _ptr(y), class_mask, _stream()))
+        return _check(lib().moe_combine(self.h, _ptr(y), class_mask, self._stream()))
 
     def expert_run_units(self, x, w: MoeWeights, unit_ids) -> int:
         """Execute the listed units (indices into units()) in the given order; updates self.cursor."""
         ids = [int(u) for u in unit_ids]
         arr = (C.c_uint32 * max(1, len(ids)))(*ids)
         return _check(lib().moe_expert_run_units(self.h, _ptr(x), C.byref(w), arr, len(ids), C.byref(self.cursor),
-                                                 _stream()))
+                                                 self._stream()))
 
     def expert_enqueue(self, x, w: MoeWeights, units_per_launch: int = 4) -> int:
         """Put all remaining units on the stream as gated launches; returns without waiting."""
-        return _check(lib().moe_expert_enqueue(self.h, _ptr(x), C.byref(w), units_per_launch, _stream()))
+        return _check(lib().moe_expert_enqueue(self.h, _ptr(x), C.byref(w), units_per_launch, self._stream()))
 
     def expert_stop(self) -> None:
         """Ask the enqueued sequence to stop at its next launch boundary."""
@@ -249,14 +256,14 @@ class Context:
 
     def expert_collect(self) -> int:
         """Wait for the stream and book what ran; updates self.cursor.  MOE_DONE when every unit has run."""
-        return _check(lib().moe_expert_collect(self.h, C.byref(self.cursor), _stream()))
+        return _check(lib().moe_expert_collect(self.h, C.byref(self.cursor), self._stream()))
 
     def combine_complete(self, y, complete=None) -> int:
         """Write the rows of y of every token whose k assignments have all been executed; `complete`
         (uint8 tensor [N], optional) receives the mask."""
         if complete is not None and complete.element_size() != 1:
             raise TypeError("complete must be a uint8 tensor")
-        return _check(lib().moe_combine_complete(self.h, _ptr(y), _ptr(complete), _stream()))
+        return _check(lib().moe_combine_complete(self.h, _ptr(y), _ptr(complete), self._stream()))
 
     def profile(self, kinds) -> None:
         """Bracket the expert kernels of the given kinds with events: True = all, False = none, or an
