@@ -32,3 +32,22 @@ def test_host_logic_under_asan_and_ubsan(tmp_path):
     print(r.stdout[-3000:])
     assert r.returncode == 0, (r.stdout[-3000:], r.stderr[-3000:])
     assert "all host-logic checks passed" in r.stdout
+
+
+def test_oracle_under_asan_and_ubsan(tmp_path):
+    """The oracle's C code through one small layer in both dtypes, every buffer a heap block of exactly
+    the documented size (tests/host_stub/oracle_asan_test.c)."""
+    exe = str(tmp_path / "oracle_asan_test")
+    cmd = ["gcc", "-O1", "-g", "-fopenmp", "-fno-fast-math", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           os.path.join(ROOT, "oracle", "moe_oracle.c"), os.path.join(STUB, "oracle_asan_test.c"), "-o", exe, "-lm"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0 and "sanitizer" in r.stderr.lower() and "cannot find" in r.stderr.lower():
+        pytest.skip("no sanitizer runtime for gcc on this machine")
+    assert r.returncode == 0, r.stderr[-4000:]
+    # leak detection off: the OpenMP runtime keeps its thread pool until exit
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0", UBSAN_OPTIONS="print_stacktrace=1",
+               OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    print(r.stdout[-2000:])
+    assert r.returncode == 0, (r.stdout[-3000:], r.stderr[-3000:])
+    assert "oracle ran clean under the sanitizers" in r.stdout
