@@ -251,7 +251,8 @@ class Context:
         return _check(lib().moe_expert_enqueue(self.h, _ptr(x), C.byref(w), units_per_launch, self._stream()))
 
     def expert_stop(self) -> None:
-        """Ask the enqueued sequence to stop at its next launch boundary."""
+        """Ask the enqueued sequence to stop: workgroups that start after the store is visible do no work,
+        so units are left whole (executed or not), also inside a launch."""
         _check(lib().moe_expert_stop(self.h))
 
     def expert_collect(self) -> int:

@@ -99,10 +99,13 @@ def sigma_out_layer(lay, w2_of) -> np.ndarray:
     return sigma
 
 
-def check_bf16_expert_out(out_gpu: np.ndarray, out_ref: np.ndarray, sigma: np.ndarray) -> dict:
+def check_bf16_expert_out(out_gpu: np.ndarray, out_ref: np.ndarray, sigma: np.ndarray, need_global: bool = True) -> dict:
     """fp32 results of the bf16 path (the expert outputs with sigma [A,H] from sigma_out_layer, or the
     unrounded y with sigma [N,H] from sigma_y) against the oracle's, every element.  Returns the
-    figures; `ok` says whether the global 2e-2 bar, the per-element bar and the RMS gate all hold."""
+    figures; `ok` says whether the global 2e-2 bar (unless need_global is off: the bar is stated for
+    the named workloads, and a shape with a short reduction and heavy-tailed activations can have
+    single elements whose own 8-sigma bar lies above 2e-2 of the global RMS), the per-element bar
+    and the RMS gate all hold."""
     A, H = out_ref.shape
     se = sr = 0.0
     mx = worst = 0.0
@@ -119,7 +122,7 @@ def check_bf16_expert_out(out_gpu: np.ndarray, out_ref: np.ndarray, sigma: np.nd
     rms = math.sqrt(sr / n) if n else 0.0
     res = {"max_rel": mx / rms if rms else 0.0, "rms_rel": math.sqrt(se / n) / rms if rms else 0.0,
            "worst_over_bar": worst, "elems": n}
-    res["ok"] = (res["max_rel"] <= 2e-2 and worst <= 1.0 and
+    res["ok"] = ((not need_global or res["max_rel"] <= 2e-2) and worst <= 1.0 and
                  (n < MIN_ELEMS_FOR_RMS_GATE or res["rms_rel"] <= RMS_GATE_OUT))
     return res
 
