@@ -4,10 +4,10 @@ row-major, bf16 packed or 4-bit; every down-projection K split): integer artefac
 the oracle, values element by element, and the same bits whether the expert work runs in one call,
 with cursor cuts, or enqueued ahead with a stop landing somewhere.
 
-The global 2e-2 bar is reported, not asserted, on these shapes: it is stated for the named workloads,
-and with reductions as short as 64-192 a single output's own error bar can lie above 2e-2 of the
-tensor's RMS.  The per-element bars and the RMS gates, which follow from the arithmetic at any shape,
-are asserted."""
+The global 2e-2 bar is asserted with bf16 and fp32 weights and only reported with 4-bit weights: it
+is stated for the named workloads, and with reductions as short as 64-192 and the heavy-tailed 4-bit
+values a single output's own error bar can lie above 2e-2 of the tensor's RMS.  The per-element bars
+and the RMS gates, which follow from the arithmetic at any shape, are asserted everywhere."""
 import time
 
 import numpy as np
@@ -78,7 +78,7 @@ def test_random_shape(i):
     assert [tuple(int(v) for v in u) for u in units] == g.ctx.units()
     np.testing.assert_allclose(r["topk_w"], lay.wt, rtol=0, atol=2e-6)
     # values, every element
-    check_values(cfg, lay, g, r["y"], need_global=False)
+    check_values(cfg, lay, g, r["y"], need_global=wfmt != "mxfp4")
     # preempted == uninterrupted
     nu = g.ctx.cursor.n_units
     ref_out = g.ctx.get("expert_out").clone()
