@@ -167,7 +167,7 @@ void launch_experts_bf16(const ExpertArgs &a, const KArgs &gu_in, const KArgs &d
             }
             std::stable_sort(groups.begin(), groups.end(), [](const Group &x, const Group &y) { return x.rows > y.rows; });
             for (const Group &g : groups) {
-                while ((n & 3) && n < kMaxSegs) b.seg[n++] = Seg{0, 0, 0};
+                while ((n & ((1 << QMOE_PK_U) - 1)) && n < kMaxSegs) b.seg[n++] = Seg{0, 0, 0};
                 for (int i = g.first; i < g.first + g.count; ++i) {
                     if (n < kMaxSegs) b.seg[n] = a.segs[i];
                     ++n;

@@ -56,6 +56,12 @@ enum { WF_ROWMAJOR = 0, WF_PACKED = 1, WF_MXFP4 = 2 };
 #define QMOE_P3_MIN_T 4
 #endif
 constexpr int kP3MinT = QMOE_P3_MIN_T;
+// A packet (32 workgroups, one XCD's CUs) is 2^QMOE_PK_U segments x 2^(5 - QMOE_PK_U) column tiles.
+// 4 x 8 fetches the least (measured on the 3584-token prefill's gate-up launch: 3.1 GB against 3.4 GB
+// for 8 x 4 and 5.0 GB for 2 x 16; the launch time follows weakly: +1 % and +6 %).
+#ifndef QMOE_PK_U
+#define QMOE_PK_U 2
+#endif
 
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -450,21 +456,22 @@ __device__ __forceinline__ bool map_block(const BArgs &b, moe_unit &un, int &ct,
     const int x = w & 7, j = w >> 3;
     const int packet = (j >> 5) * 8 + x, within = j & 31;
     const int n = b.nseg > 0 ? b.nseg : b.k.nu;
-    const int ugroups = (n + 3) >> 2;
+    constexpr int PU = QMOE_PK_U, PC = 5 - PU;      // log2 of units and of column tiles per packet
+    const int ugroups = (n + (1 << PU) - 1) >> PU;
     // Streaming launches list their segments longest first: the packets walk the column tiles of one
     // group of segments before the next group, so the long segments really start first.  Launches
     // that share weights walk the groups first: the packets of one column block run side by side.
     int ctb, ug;
     if (STREAM) {
-        const int ctbs = (b.k.col_tiles * b.ksplit + 7) >> 3;
+        const int ctbs = (b.k.col_tiles * b.ksplit + (1 << PC) - 1) >> PC;
         ug = packet / ctbs;
         ctb = packet - ug * ctbs;
     } else {
         ctb = packet / ugroups;
         ug = packet - ctb * ugroups;
     }
-    const int pos = ug * 4 + (within >> 3);
-    const int cq = ctb * 8 + (within & 7);
+    const int pos = (ug << PU) + (within >> PC);
+    const int cq = (ctb << PC) + (within & ((1 << PC) - 1));
     if (pos >= n || cq >= b.k.col_tiles * b.ksplit) return false;
     if (b.nseg > 0) {
         const Seg g = b.seg[pos];
@@ -514,7 +521,7 @@ __global__ __launch_bounds__(256) void expert_bf16(const BArgs b) {
 template <int TCAP, bool GATEUP, int WF, bool STREAM>
 void launch1(const BArgs &b, hipStream_t s) {
     const unsigned n = b.nseg > 0 ? (unsigned)b.nseg : (unsigned)b.k.nu;
-    const unsigned ugroups = (n + 3) / 4, ctb = (b.k.col_tiles * b.ksplit + 7) / 8;
+    const unsigned ugroups = (n + (1u << QMOE_PK_U) - 1) >> QMOE_PK_U, ctb = (b.k.col_tiles * b.ksplit + (32u >> QMOE_PK_U) - 1) / (32u >> QMOE_PK_U);
     const unsigned packets = ugroups * ctb;
     const unsigned grid = (packets + 7) / 8 * 8 * 32;
     hipLaunchKernelGGL((expert_bf16<TCAP, GATEUP, WF, STREAM>), dim3(grid), dim3(256), 0, s, b);
