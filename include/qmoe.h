@@ -20,7 +20,8 @@
  *    pointers.  The library allocates no device memory and creates no stream.  (It allocates one
  *    small pinned host buffer per context at the first moe_route, freed by moe_destroy.)
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
- *    work and return, except moe_permute, which waits until the per-expert counts are on the host.
+ *    work and return, except moe_permute, which waits until the per-expert counts are on the host,
+ *    moe_expert_collect, which waits for the stream, and moe_profile_read, which waits for its events.
  *    All calls on one context must be issued on one stream, or be ordered by the caller.
  *  - Return value: moe_status.  Negative = error; in that case nothing was enqueued and the
  *    context is unchanged (MOE_E_HIP excepted, where the HIP runtime failed half-way).
